@@ -1,0 +1,200 @@
+// CPU oracle for the S3-Attention hot path.  TEST INFRASTRUCTURE ONLY.
+//
+// Plain, slow, fp64, written straight from the paper's definitions so that it can be checked
+// against the paper by eye.  It shares no code with the HIP library and is loaded only by the
+// tests, by the smoke check and by the benchmark's cpu_baseline leg; the product path never
+// calls it.  Every function below is pinned by CPU tests against closed forms, hand-computed
+// cases, brute force and library routines (no function here is "parity unpinned").
+//
+// All pointers are host pointers.  bf16 inputs arrive as uint16 bit patterns and are widened
+// exactly; nothing is rounded before the fp64 arithmetic.
+#include <algorithm>
+#include <cmath>
+#include <cstdint>
+#include <cstring>
+#include <map>
+#include <vector>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+namespace {
+
+inline double widen(const void* p, int dtype, size_t i) {
+    if (dtype == 1) return (double)((const float*)p)[i];
+    uint32_t u = (uint32_t)((const uint16_t*)p)[i] << 16;   // bf16 -> fp32 is exact
+    float f;
+    std::memcpy(&f, &u, 4);
+    return (double)f;
+}
+
+struct Index {                                   // Sec. 3.4: inverted index I[f] -> positions
+    std::map<int32_t, std::vector<int32_t>> lists;
+    int64_t n_postings = 0;
+};
+
+}  // namespace
+
+extern "C" {
+
+// Sec. 3.3, encoder equation: z = W_enc (x - b_dec) + b_enc with b_dec folded into b_enc
+// (b_enc_eff = b_enc - W_enc b_dec), then the Top-K equation.  Selection is made on the
+// pre-activation z (full sort by z descending, feature id ascending on exact ties), so that a
+// row always yields exactly k ids; the stored activation is ReLU(z).
+//   x [T, d] and w [n_feat, d] in dtype (0 = bf16 bits, 1 = fp32), b [n_feat] fp32.
+//   ids [T, k], vals [T, k] (ReLU(z) rounded to fp32), zsel [T, k] fp64 (may be null),
+//   gap [T] fp64 (may be null): (z_(k) - z_(k+1)) / |z_(k)|, +inf when k == n_feat.
+//   zdense [T, n_feat] fp64 (may be null).
+int orc_encode_topk(const void* x, int dtype, int T, int d, const void* w, const float* b,
+                    int n_feat, int k, int32_t* ids, float* vals, double* zsel, double* gap,
+                    double* zdense) {
+    if (T < 0 || d <= 0 || n_feat <= 0 || k <= 0 || k > n_feat) return -1;
+    std::vector<double> wd((size_t)n_feat * d);
+    for (size_t i = 0; i < wd.size(); ++i) wd[i] = widen(w, dtype, i);
+#pragma omp parallel
+    {
+        std::vector<double> xr(d), z(n_feat);
+        std::vector<int32_t> order(n_feat);
+#pragma omp for schedule(dynamic, 8)
+        for (int t = 0; t < T; ++t) {
+            for (int c = 0; c < d; ++c) xr[c] = widen(x, dtype, (size_t)t * d + c);
+            for (int f = 0; f < n_feat; ++f) {
+                double acc = 0.0;
+                const double* wf = &wd[(size_t)f * d];
+                for (int c = 0; c < d; ++c) acc += xr[c] * wf[c];
+                z[f] = acc + (double)b[f];
+            }
+            if (zdense) std::memcpy(zdense + (size_t)t * n_feat, z.data(), sizeof(double) * n_feat);
+            for (int f = 0; f < n_feat; ++f) order[f] = f;
+            std::sort(order.begin(), order.end(), [&](int32_t a, int32_t c) {
+                if (z[a] != z[c]) return z[a] > z[c];
+                return a < c;
+            });
+            for (int j = 0; j < k; ++j) {
+                int32_t f = order[j];
+                ids[(size_t)t * k + j] = f;
+                vals[(size_t)t * k + j] = (float)std::max(z[f], 0.0);
+                if (zsel) zsel[(size_t)t * k + j] = z[f];
+            }
+            if (gap) {
+                if (k == n_feat) gap[t] = INFINITY;
+                else {
+                    double zk = z[order[k - 1]], zn = z[order[k]];
+                    gap[t] = (zk - zn) / std::fabs(zk);
+                }
+            }
+        }
+    }
+    return 0;
+}
+
+// Sec. 3.4, index update equation: for every feature f in F_t, I[f] <- I[f] U {t}, tokens taken
+// in the order given; positions are absolute.
+void* orc_index_new(void) { return new Index(); }
+void orc_index_free(void* h) { delete (Index*)h; }
+
+int orc_index_append(void* h, const int32_t* ids, const int32_t* positions, int T, int k) {
+    Index* ix = (Index*)h;
+    for (int t = 0; t < T; ++t)
+        for (int j = 0; j < k; ++j) {
+            ix->lists[ids[(size_t)t * k + j]].push_back(positions[t]);
+            ix->n_postings++;
+        }
+    return 0;
+}
+
+int64_t orc_index_postings(void* h) { return ((Index*)h)->n_postings; }
+
+// Contiguous form of the same index (the paper's recommended production layout, Sec. 3.4
+// "CPU Index Size"): lists concatenated by ascending feature id; offsets [n_feat + 1].
+int orc_index_export(void* h, int n_feat, int32_t* offsets, int32_t* positions) {
+    Index* ix = (Index*)h;
+    int64_t o = 0;
+    for (int f = 0; f < n_feat; ++f) {
+        offsets[f] = (int32_t)o;
+        auto it = ix->lists.find(f);
+        if (it == ix->lists.end()) continue;
+        for (int32_t p : it->second) positions[o++] = p;
+    }
+    offsets[n_feat] = (int32_t)o;
+    for (auto& kv : ix->lists)
+        if (kv.first < 0 || kv.first >= n_feat) return -1;
+    return 0;
+}
+
+// App. D.2 / App. E: IDF(f) = 1 / (log(1 + freq(f)) + 1), natural log, freq = posting-list length.
+double orc_idf(int64_t freq) { return 1.0 / (std::log(1.0 + (double)freq) + 1.0); }
+
+// Sec. 3.5 scoring equation and App. D.2: S[t] += a_f^(Q) * IDF(f) for every position t in I[f],
+// for every (query vector, slot) pair; pairs naming the same feature add up.  App. E's hard
+// threshold: a feature with freq > max_freq is skipped (max_freq <= 0 disables the rule).
+// Adds one (layer, head) index into S [L] (fp64); call once per head to sum over heads/layers.
+int orc_score_accumulate(void* h, const int32_t* qids, const float* qvals, int nq, int k,
+                         int32_t max_freq, double* S, int64_t L) {
+    Index* ix = (Index*)h;
+    for (int q = 0; q < nq; ++q)
+        for (int j = 0; j < k; ++j) {
+            int32_t f = qids[(size_t)q * k + j];
+            auto it = ix->lists.find(f);
+            if (it == ix->lists.end()) continue;
+            int64_t freq = (int64_t)it->second.size();
+            if (max_freq > 0 && freq > max_freq) continue;
+            double wgt = (double)qvals[(size_t)q * k + j] * orc_idf(freq);
+            for (int32_t p : it->second) {
+                if (p < 0 || p >= L) return -1;
+                S[p] += wgt;
+            }
+        }
+    return 0;
+}
+
+// Sec. 3.5 "Adaptive Granularity", smoothing step, read as a box kernel of width span_len
+// summed (not averaged) over valid windows only: W[s] = sum_{t=s}^{s+len-1} S[t],
+// s in [0, L - len]; len is clamped to L.  Returns the number of windows.
+int64_t orc_pool(const double* S, int64_t L, int span_len, double* W) {
+    int64_t len = std::min<int64_t>(span_len, L);
+    int64_t nw = L - len + 1;
+    for (int64_t s = 0; s < nw; ++s) {
+        double acc = 0.0;
+        for (int64_t t = s; t < s + len; ++t) acc += S[t];
+        W[s] = acc;
+    }
+    return nw;
+}
+
+// Sec. 3.5, peak selection with non-maximum suppression, read as: repeat top_b times -- take the
+// best remaining window (ties -> smallest start); with nms, suppress every window overlapping it
+// (|s' - s| < span_len).  Stops early when nothing is left.  Returns n_found.
+int orc_topb(const double* W, int64_t nw, int span_len, int top_b, int nms, int32_t* starts,
+             double* scores) {
+    std::vector<char> dead(nw, 0);
+    int found = 0;
+    for (int r = 0; r < top_b; ++r) {
+        int64_t best = -1;
+        for (int64_t s = 0; s < nw; ++s)
+            if (!dead[s] && (best < 0 || W[s] > W[best])) best = s;
+        if (best < 0) break;
+        starts[found] = (int32_t)best;
+        scores[found] = W[best];
+        ++found;
+        if (nms) {
+            for (int64_t s = std::max<int64_t>(0, best - span_len + 1);
+                 s < std::min<int64_t>(nw, best + span_len); ++s)
+                dead[s] = 1;
+        } else {
+            dead[best] = 1;
+        }
+    }
+    return found;
+}
+
+// Number of host threads orc_encode_topk uses (rows are independent; nothing else is threaded).
+int orc_threads(void) {
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}
+
+}  // extern "C"

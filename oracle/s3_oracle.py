@@ -1,0 +1,143 @@
+"""ctypes loader for the CPU oracle (oracle/s3_oracle.cpp).  TEST INFRASTRUCTURE ONLY.
+
+Imported by tests/, by the smoke check and by the benchmark's cpu_baseline leg; never by the
+product package.  Argument marshalling only: all arithmetic is in the C++ file.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+import subprocess
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "s3_oracle.cpp")
+_LIB = os.path.join(_HERE, "libs3oracle.so")
+_lib = None
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle with the host compiler (g++, OpenMP over rows)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        subprocess.check_call(["g++", "-O2", "-std=c++17", "-fopenmp", "-fPIC", "-shared", "-Wall",
+                               "-o", _LIB, _SRC])
+    return _LIB
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        L = C.CDLL(build())
+        vp, i32, i64 = C.c_void_p, C.c_int32, C.c_int64
+        L.orc_encode_topk.argtypes = [vp, C.c_int, C.c_int, C.c_int, vp, vp, C.c_int, C.c_int, vp, vp, vp, vp, vp]
+        L.orc_encode_topk.restype = C.c_int
+        L.orc_index_new.restype = vp
+        L.orc_index_free.argtypes = [vp]
+        L.orc_index_append.argtypes = [vp, vp, vp, C.c_int, C.c_int]
+        L.orc_index_postings.argtypes = [vp]
+        L.orc_index_postings.restype = i64
+        L.orc_index_export.argtypes = [vp, C.c_int, vp, vp]
+        L.orc_idf.argtypes = [i64]
+        L.orc_idf.restype = C.c_double
+        L.orc_score_accumulate.argtypes = [vp, vp, vp, C.c_int, C.c_int, i32, vp, i64]
+        L.orc_pool.argtypes = [vp, i64, C.c_int, vp]
+        L.orc_pool.restype = i64
+        L.orc_topb.argtypes = [vp, i64, C.c_int, C.c_int, C.c_int, vp, vp]
+        L.orc_threads.restype = C.c_int
+        _lib = L
+    return _lib
+
+
+def _p(a):
+    return None if a is None else a.ctypes.data_as(C.c_void_p)
+
+
+def _dt(dtype: str) -> int:
+    return {"bf16": 0, "fp32": 1}[dtype]
+
+
+def encode_topk(x, w, b, k, dtype, want_dense=False):
+    """x [T, d], w [n_feat, d] as stored (uint16 bf16 bits or float32), b [n_feat] float32.
+    Returns dict(ids [T,k] int32, vals [T,k] float32, zsel [T,k] f64, gap [T] f64, z [T,n_feat] f64|None)."""
+    x = np.ascontiguousarray(x)
+    w = np.ascontiguousarray(w)
+    b = np.ascontiguousarray(b, dtype=np.float32)
+    want = np.float32 if dtype == "fp32" else np.uint16
+    assert x.dtype == want and w.dtype == want
+    T, d = x.shape
+    n_feat = w.shape[0]
+    ids = np.empty((T, k), np.int32)
+    vals = np.empty((T, k), np.float32)
+    zsel = np.empty((T, k), np.float64)
+    gap = np.empty((T,), np.float64)
+    z = np.empty((T, n_feat), np.float64) if want_dense else None
+    rc = lib().orc_encode_topk(_p(x), _dt(dtype), T, d, _p(w), _p(b), n_feat, k, _p(ids), _p(vals), _p(zsel),
+                               _p(gap), _p(z))
+    if rc != 0:
+        raise ValueError("orc_encode_topk: invalid arguments")
+    return {"ids": ids, "vals": vals, "zsel": zsel, "gap": gap, "z": z}
+
+
+class Index:
+    """Inverted index of one (layer, head): feature id -> positions in insertion order."""
+
+    def __init__(self, n_feat: int):
+        self.n_feat = n_feat
+        self._h = lib().orc_index_new()
+
+    def append(self, ids, positions):
+        ids = np.ascontiguousarray(ids, dtype=np.int32)
+        positions = np.ascontiguousarray(positions, dtype=np.int32)
+        assert ids.ndim == 2 and positions.shape == (ids.shape[0],)
+        lib().orc_index_append(self._h, _p(ids), _p(positions), ids.shape[0], ids.shape[1])
+
+    @property
+    def n_postings(self) -> int:
+        return int(lib().orc_index_postings(self._h))
+
+    def csr(self):
+        offsets = np.empty(self.n_feat + 1, np.int32)
+        positions = np.empty(max(self.n_postings, 1), np.int32)
+        rc = lib().orc_index_export(self._h, self.n_feat, _p(offsets), _p(positions))
+        if rc != 0:
+            raise ValueError("feature id outside [0, n_feat)")
+        return offsets, positions[: self.n_postings]
+
+    def score_accumulate(self, qids, qvals, S, max_freq=0):
+        qids = np.ascontiguousarray(qids, dtype=np.int32)
+        qvals = np.ascontiguousarray(qvals, dtype=np.float32)
+        assert S.dtype == np.float64 and S.flags.c_contiguous
+        rc = lib().orc_score_accumulate(self._h, _p(qids), _p(qvals), qids.shape[0], qids.shape[1], int(max_freq),
+                                        _p(S), S.shape[0])
+        if rc != 0:
+            raise ValueError("position outside [0, L)")
+
+    def __del__(self):
+        if getattr(self, "_h", None):
+            lib().orc_index_free(self._h)
+            self._h = None
+
+
+def idf(freq: int) -> float:
+    return float(lib().orc_idf(int(freq)))
+
+
+def pool(S, span_len):
+    S = np.ascontiguousarray(S, dtype=np.float64)
+    L = S.shape[0]
+    W = np.empty(L - min(span_len, L) + 1, np.float64)
+    nw = lib().orc_pool(_p(S), L, int(span_len), _p(W))
+    assert nw == W.shape[0]
+    return W
+
+
+def topb(W, span_len, top_b, nms=True):
+    W = np.ascontiguousarray(W, dtype=np.float64)
+    starts = np.empty(top_b, np.int32)
+    scores = np.empty(top_b, np.float64)
+    n = lib().orc_topb(_p(W), W.shape[0], int(span_len), int(top_b), int(bool(nms)), _p(starts), _p(scores))
+    return starts[:n].copy(), scores[:n].copy()
+
+
+def threads() -> int:
+    return int(lib().orc_threads())
