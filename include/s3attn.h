@@ -1,0 +1,145 @@
+/* s3attn.h -- C ABI of the MI355X (gfx950) hot path of S3-Attention:
+ *
+ *   sae_encode_topk : key/query chunk -> Top-k SAE feature ids + activations   (Sec. 3.3)
+ *   index_*         : feature ids -> feature -> token-position inverted index   (Sec. 3.4)
+ *   coactivate_score: query features + index -> position scores -> Top-B spans  (Sec. 3.5, App. D.2, App. E)
+ *
+ * Conventions
+ *   - Every array pointer is a DEVICE pointer owned by the caller unless marked "host".
+ *   - Every call is asynchronous on `stream` (a hipStream_t passed as void*; NULL = the null
+ *     stream); outputs are valid once the stream has reached the call.  No call synchronises
+ *     the host with the device and no call after s3_index_create / workspace set-up allocates.
+ *   - Inputs are never modified.  Outputs must not alias inputs.
+ *   - Return value: S3_OK (0) or a negative S3_E* code; s3_last_error() gives the message.
+ *     Arguments are validated on the host before anything is launched; on error nothing has
+ *     been launched.
+ *   - One GPU: the device that is current when s3_index_create / a call is made.
+ */
+#ifndef S3ATTN_H
+#define S3ATTN_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+    S3_OK = 0,
+    S3_EINVAL = -1,    /* null pointer, shape or parameter outside the supported range */
+    S3_ESTATE = -2,    /* call not allowed in the index's current state */
+    S3_ECAPACITY = -3, /* more tokens than the index was created for, or workspace too small */
+    S3_EHIP = -4       /* a HIP runtime call failed */
+};
+
+enum { S3_BF16 = 0, S3_FP32 = 1 };
+
+#define S3_MAX_K 64          /* largest supported Top-k */
+#define S3_MAX_FEAT 65536    /* largest supported SAE width */
+
+/* Message of the last error on this host thread (valid until the next failing call). */
+const char* s3_last_error(void);
+
+/* ------------------------------------------------------------------------------------------
+ * Sec. 3.3, encoder equation z = ReLU(W_enc (x - b_dec) + b_enc) followed by the Top-K
+ * equation, for a batch of independent (layer, head) SAEs.  The same call encodes key chunks
+ * (Sec. 3.4, per-chunk feature extraction) and query vectors (Sec. 3.5 "Query Decoding"); the
+ * caller passes the same w_enc/b_enc for both (shared codebook, Alg. 1 Phase 0).
+ *
+ *   x      [n_heads, T, d_head]       bf16 or fp32 (dtype), row-major, 16-byte aligned
+ *   w_enc  [n_heads, n_feat, d_head]  same dtype, feature-major (one feature's vector contiguous)
+ *   b_enc  [n_heads, n_feat]          fp32; b_dec must be folded in by the caller:
+ *                                     b_enc_eff = b_enc - W_enc b_dec
+ *   ids    [n_heads, T, k] int32, vals [n_heads, T, k] fp32 (outputs)
+ *
+ * Per row the k features with the largest pre-activation z are selected (ties: lower id), so a
+ * row always has exactly k distinct ids; vals = max(z, 0).  Within a row the order is
+ * (z descending, id ascending).  z is accumulated in fp32 and never written to memory.
+ * Inputs are assumed finite.
+ * Limits: d_head in {64, 128, 256}; 1 <= k <= min(n_feat, S3_MAX_K); n_feat <= S3_MAX_FEAT;
+ * T >= 0 (T == 0 is a no-op); n_heads >= 1.  Otherwise S3_EINVAL.  No workspace is needed.
+ */
+int s3_sae_encode_topk(const void* x, int dtype, int T, int d_head, const void* w_enc,
+                       const float* b_enc, int n_feat, int k, int n_heads, int32_t* ids,
+                       float* vals, void* stream);
+
+/* ------------------------------------------------------------------------------------------
+ * Sec. 3.4, inverted semantic index: for all f in F_t, I[f] <- I[f] U {t}, held on the GPU in
+ * the contiguous form the paper recommends (Sec. 3.4 "CPU Index Size"): per head a CSR with
+ * offsets[n_feat + 1] and positions[P], lists in ascending feature id, positions inside a list
+ * in the order the tokens were appended.  P = tokens * k per head (same section).
+ *
+ * s3_index_create allocates everything for n_heads independent indexes of up to max_tokens
+ * tokens each (host call; the handle is library-owned; destroy with s3_index_destroy).
+ * Limits: n_feat <= S3_MAX_FEAT, k <= S3_MAX_K, max_tokens * k < 2^31, max_tokens <= 2^24.
+ */
+typedef struct s3_index s3_index;
+int s3_index_create(int n_heads, int n_feat, int k, int64_t max_tokens, s3_index** out);
+void s3_index_destroy(s3_index* idx);
+
+/* Append one chunk (Alg. 1, Phase 1 inner loop "Update I with feats").
+ *   ids [n_heads, T, k] int32 in [0, n_feat); positions [T] int32 absolute positions shared by
+ *   all heads, or NULL for base_pos + row.  Chunks may have any length T >= 0.
+ * S3_ESTATE after finalize; S3_ECAPACITY if the total would exceed max_tokens.
+ * Ids outside [0, n_feat) are undefined behaviour (they are not checked on the device). */
+int s3_index_append(s3_index* idx, const int32_t* ids, int T, const int32_t* positions,
+                    int32_t base_pos, void* stream);
+
+/* Turn everything appended so far into the CSR.  May be called once; appending afterwards is
+ * S3_ESTATE.  The result does not depend on how the stream was cut into chunks. */
+int s3_index_finalize(s3_index* idx, void* stream);
+
+/* Borrowed device views of one head's CSR (valid until destroy): offsets [n_feat + 1] int32,
+ * positions [*n_postings] int32.  Host call; S3_ESTATE before finalize. */
+int s3_index_csr(const s3_index* idx, int head, const int32_t** offsets,
+                 const int32_t** positions, int64_t* n_postings);
+
+/* Copy one head's CSR into caller-owned device arrays offsets_out [n_feat + 1] and
+ * positions_out [n_postings] (either may be NULL to skip it); asynchronous on `stream`. */
+int s3_index_export(const s3_index* idx, int head, int32_t* offsets_out, int32_t* positions_out,
+                    void* stream);
+
+/* Tokens appended so far (host value). */
+int64_t s3_index_tokens(const s3_index* idx);
+
+/* One-shot form for a single index with caller-owned outputs: offsets [n_feat + 1],
+ * out_positions [T * k]; positions [T] or NULL (= row).  ws must hold
+ * s3_index_build_workspace(T, k, n_feat) bytes (256-byte aligned). */
+size_t s3_index_build_workspace(int T, int k, int n_feat);
+int s3_index_build(const int32_t* ids, const int32_t* positions, int T, int k, int n_feat,
+                   int32_t* offsets, int32_t* out_positions, void* ws, size_t ws_bytes,
+                   void* stream);
+
+/* ------------------------------------------------------------------------------------------
+ * Sec. 3.5 scoring equation with App. D.2's weights:
+ *     S[t] = sum over heads h, over query pairs (q, j) with f = qids[h, q, j]:
+ *            qvals[h, q, j] * IDF_h(f) * 1[t in I_h[f]],   IDF(f) = 1 / (ln(1 + freq(f)) + 1),
+ * freq(f) = length of I_h[f]; a feature with freq > max_freq is skipped when max_freq > 0
+ * (App. E's hard threshold; the paper's value is 5000).  Then the smoothing and peak
+ * selection of Sec. 3.5 "Adaptive Granularity", read as a box kernel and fixed-length spans:
+ *     W[s] = sum_{t = s}^{s + span_len - 1} S[t],  s in [0, L - span_len]   (span_len clamped to L)
+ *     repeat top_b times: best remaining window (ties: smallest s); if nms, drop every window
+ *     overlapping it (|s' - s| < span_len); stop early if none is left.
+ * L = n_positions: positions in the index must lie in [0, n_positions).
+ *
+ *   qids/qvals [n_heads, nq, k]  (the output layout of s3_sae_encode_topk on the query vectors;
+ *                                 the caller has already mapped each Q head to its KV head)
+ *   scores_out [n_positions] fp32 or NULL; span_start [top_b] int32; span_score [top_b] fp32;
+ *   n_found [1] int32.  Entries past n_found are set to -1 / 0.
+ *   ws: s3_coactivate_score_workspace(idx, n_positions) bytes, 256-byte aligned.
+ * Sums are accumulated in 64-bit fixed point, so the result is independent of execution order
+ * (bit-identical from run to run) and W[s] is exactly the sum of its members before the final
+ * rounding to fp32.
+ * Limits: 1 <= span_len; 1 <= top_b <= 1024; nq >= 0; qvals finite and >= 0.
+ */
+size_t s3_coactivate_score_workspace(const s3_index* idx, int64_t n_positions);
+int s3_coactivate_score(const s3_index* idx, const int32_t* qids, const float* qvals, int nq,
+                        int64_t n_positions, int span_len, int top_b, int32_t max_freq, int nms,
+                        float* scores_out, int32_t* span_start, float* span_score,
+                        int32_t* n_found, void* ws, size_t ws_bytes, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* S3ATTN_H */

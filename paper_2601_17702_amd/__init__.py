@@ -1,0 +1,182 @@
+"""Thin Python binding of libs3attn.so (C ABI in include/s3attn.h).
+
+Argument marshalling only: every step of the path runs in the HIP kernels of the library.
+PyTorch supplies device memory and the current stream.  There is no CPU fallback: if the
+library is not built, loading raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libs3attn.so")
+_lib = None
+
+S3_BF16, S3_FP32 = 0, 1
+MAX_K, MAX_FEAT = 64, 65536
+
+
+class S3Error(RuntimeError):
+    def __init__(self, code: int, msg: str):
+        super().__init__(f"s3attn error {code}: {msg}")
+        self.code = code
+
+
+def lib():
+    """Load the HIP library (built in-tree by paper_2601_17702_amd/build.py)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise ImportError(f"{LIB_PATH} is missing: build it with `python -m paper_2601_17702_amd.build` "
+                              "(there is no fallback path)")
+        L = C.CDLL(LIB_PATH)
+        vp, i32, i64, ci, sz = C.c_void_p, C.c_int32, C.c_int64, C.c_int, C.c_size_t
+        L.s3_last_error.restype = C.c_char_p
+        L.s3_sae_encode_topk.argtypes = [vp, ci, ci, ci, vp, vp, ci, ci, ci, vp, vp, vp]
+        L.s3_index_create.argtypes = [ci, ci, ci, i64, C.POINTER(vp)]
+        L.s3_index_destroy.argtypes = [vp]
+        L.s3_index_destroy.restype = None
+        L.s3_index_append.argtypes = [vp, vp, ci, vp, i32, vp]
+        L.s3_index_finalize.argtypes = [vp, vp]
+        L.s3_index_csr.argtypes = [vp, ci, C.POINTER(vp), C.POINTER(vp), C.POINTER(i64)]
+        L.s3_index_export.argtypes = [vp, ci, vp, vp, vp]
+        L.s3_index_export.restype = ci
+        L.s3_index_tokens.argtypes = [vp]
+        L.s3_index_tokens.restype = i64
+        L.s3_index_build_workspace.argtypes = [ci, ci, ci]
+        L.s3_index_build_workspace.restype = sz
+        L.s3_index_build.argtypes = [vp, vp, ci, ci, ci, vp, vp, vp, sz, vp]
+        L.s3_coactivate_score_workspace.argtypes = [vp, i64]
+        L.s3_coactivate_score_workspace.restype = sz
+        L.s3_coactivate_score.argtypes = [vp, vp, vp, ci, i64, ci, ci, i32, ci, vp, vp, vp, vp, vp, sz, vp]
+        for name in ("s3_sae_encode_topk", "s3_index_create", "s3_index_append", "s3_index_finalize",
+                     "s3_index_csr", "s3_index_build", "s3_coactivate_score"):
+            getattr(L, name).restype = ci
+        _lib = L
+    return _lib
+
+
+def _check(rc: int):
+    if rc != 0:
+        raise S3Error(rc, lib().s3_last_error().decode())
+
+
+def _stream():
+    import torch
+    return C.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _ptr(t):
+    return C.c_void_p(t.data_ptr()) if t is not None else None
+
+
+def _dtype_code(t) -> int:
+    import torch
+    if t.dtype == torch.bfloat16:
+        return S3_BF16
+    if t.dtype == torch.float32:
+        return S3_FP32
+    raise TypeError(f"x must be bfloat16 or float32, got {t.dtype}")
+
+
+def sae_encode_topk(x, w_enc, b_enc, k: int, ids=None, vals=None):
+    """x [n_heads, T, d_head], w_enc [n_heads, n_feat, d_head] (same dtype), b_enc [n_heads, n_feat] fp32,
+    all on the GPU and contiguous.  Returns (ids int32 [n_heads, T, k], vals fp32 [n_heads, T, k])."""
+    import torch
+    assert x.is_cuda and x.is_contiguous() and w_enc.is_contiguous() and b_enc.is_contiguous()
+    assert x.dim() == 3 and w_enc.dim() == 3 and b_enc.dim() == 2
+    n_heads, T, d = x.shape
+    n_feat = w_enc.shape[1]
+    assert w_enc.shape == (n_heads, n_feat, d) and b_enc.shape == (n_heads, n_feat)
+    assert w_enc.dtype == x.dtype and b_enc.dtype == torch.float32
+    if ids is None:
+        ids = torch.empty((n_heads, T, k), dtype=torch.int32, device=x.device)
+    if vals is None:
+        vals = torch.empty((n_heads, T, k), dtype=torch.float32, device=x.device)
+    assert ids.is_contiguous() and vals.is_contiguous() and ids.dtype == torch.int32 and vals.dtype == torch.float32
+    assert ids.numel() == n_heads * T * k and vals.numel() == n_heads * T * k
+    _check(lib().s3_sae_encode_topk(_ptr(x), _dtype_code(x), T, d, _ptr(w_enc), _ptr(b_enc), n_feat, k, n_heads,
+                                    _ptr(ids), _ptr(vals), _stream()))
+    return ids, vals
+
+
+class Index:
+    """n_heads inverted indexes (feature -> positions) living on the GPU (s3_index_* calls)."""
+
+    def __init__(self, n_heads: int, n_feat: int, k: int, max_tokens: int):
+        h = C.c_void_p()
+        _check(lib().s3_index_create(n_heads, n_feat, k, max_tokens, C.byref(h)))
+        self._h = h
+        self.n_heads, self.n_feat, self.k, self.max_tokens = n_heads, n_feat, k, max_tokens
+
+    def append(self, ids, positions=None, base_pos: int = 0):
+        import torch
+        assert ids.is_cuda and ids.is_contiguous() and ids.dtype == torch.int32 and ids.dim() == 3
+        assert ids.shape[0] == self.n_heads and ids.shape[2] == self.k
+        if positions is not None:
+            assert positions.is_cuda and positions.dtype == torch.int32 and positions.numel() == ids.shape[1]
+        _check(lib().s3_index_append(self._h, _ptr(ids), ids.shape[1], _ptr(positions), base_pos, _stream()))
+
+    def finalize(self):
+        _check(lib().s3_index_finalize(self._h, _stream()))
+
+    @property
+    def tokens(self) -> int:
+        return int(lib().s3_index_tokens(self._h))
+
+    def csr(self, head: int):
+        """Copies of one head's (offsets [n_feat + 1], positions [P]) as torch int32 tensors."""
+        import torch
+        off, pos, n = C.c_void_p(), C.c_void_p(), C.c_int64()
+        _check(lib().s3_index_csr(self._h, head, C.byref(off), C.byref(pos), C.byref(n)))
+        o = torch.empty(self.n_feat + 1, dtype=torch.int32, device="cuda")
+        p = torch.empty(n.value, dtype=torch.int32, device="cuda")
+        _check(lib().s3_index_export(self._h, head, _ptr(o), _ptr(p) if n.value else None, _stream()))
+        return o, p
+
+    def score_workspace(self, n_positions: int) -> int:
+        return int(lib().s3_coactivate_score_workspace(self._h, n_positions))
+
+    def coactivate_score(self, qids, qvals, n_positions: int, span_len: int, top_b: int, max_freq: int = 0,
+                         nms: bool = True, want_scores: bool = False, ws=None):
+        """Returns (span_start int32 [top_b], span_score fp32 [top_b], n_found int32 [1], scores fp32 [L] | None)."""
+        import torch
+        assert qids.is_cuda and qids.is_contiguous() and qvals.is_contiguous()
+        assert qids.dtype == torch.int32 and qvals.dtype == torch.float32 and qids.dim() == 3
+        assert qids.shape[0] == self.n_heads and qids.shape[2] == self.k and qvals.shape == qids.shape
+        dev = qids.device
+        need = self.score_workspace(n_positions)
+        if ws is None:
+            ws = torch.empty(need, dtype=torch.uint8, device=dev)
+        assert ws.numel() >= need
+        starts = torch.empty(top_b, dtype=torch.int32, device=dev)
+        scores = torch.empty(top_b, dtype=torch.float32, device=dev)
+        found = torch.empty(1, dtype=torch.int32, device=dev)
+        S = torch.empty(n_positions, dtype=torch.float32, device=dev) if want_scores else None
+        _check(lib().s3_coactivate_score(self._h, _ptr(qids), _ptr(qvals), qids.shape[1], n_positions, span_len,
+                                         top_b, max_freq, int(bool(nms)), _ptr(S), _ptr(starts), _ptr(scores),
+                                         _ptr(found), _ptr(ws), ws.numel(), _stream()))
+        return starts, scores, found, S
+
+    def destroy(self):
+        if getattr(self, "_h", None):
+            lib().s3_index_destroy(self._h)
+            self._h = None
+
+    def __del__(self):
+        self.destroy()
+
+
+def index_build(ids, n_feat: int, positions=None):
+    """One-shot CSR of a single index: ids [T, k] int32 -> (offsets [n_feat + 1], positions [T * k])."""
+    import torch
+    assert ids.is_cuda and ids.is_contiguous() and ids.dtype == torch.int32 and ids.dim() == 2
+    T, k = ids.shape
+    need = int(lib().s3_index_build_workspace(T, k, n_feat))
+    ws = torch.empty(max(need, 1), dtype=torch.uint8, device=ids.device)
+    off = torch.empty(n_feat + 1, dtype=torch.int32, device=ids.device)
+    pos = torch.empty(T * k, dtype=torch.int32, device=ids.device)
+    _check(lib().s3_index_build(_ptr(ids), _ptr(positions), T, k, n_feat, _ptr(off), _ptr(pos), _ptr(ws),
+                                ws.numel(), _stream()))
+    return off, pos
