@@ -1,15 +1,541 @@
+// Inverted index build on the GPU (Sec. 3.4: I[f] <- I[f] U {t}; contiguous CSR layout of
+// Sec. 3.4 "CPU Index Size").
+//
+// A direct counting-sort scatter of (feature -> position) writes 4 bytes to one of n_feat
+// places per posting: nothing coalesces.  The build is therefore a two-level (most-significant
+// digit first) stable counting sort whose every global write is a contiguous run:
+//
+//   append   : each tile of <= 8192 postings (<= 8192/k tokens of one head) is sorted in LDS by
+//              the feature's coarse bucket (f >> S, at most 256 buckets) and written out as one
+//              contiguous tile of packed (row << S | f & mask) words, plus a small table of
+//              (offset, count) per (bucket, tile).  The order inside a bucket stays the append
+//              order (stable), so positions inside a posting list come out ascending.
+//   finalize : per (head, bucket) the pieces of all tiles are gathered in tile order, sorted in
+//              LDS by the low feature bits (stable again) and written to their final place in the
+//              CSR; the per-feature counts of the bucket give offsets[].
+//
+// All ranks come from prefix sums over fixed thread orders: no atomics decide a position, so the
+// CSR is bit-identical from run to run and independent of how the stream was chunked.
 #include "s3_common.h"
-struct s3_index { int dummy; };
-extern "C" {
-int s3_index_create(int, int, int, int64_t, s3_index**) { return s3_fail(S3_ESTATE, "not implemented"); }
-void s3_index_destroy(s3_index*) {}
-int s3_index_append(s3_index*, const int32_t*, int, const int32_t*, int32_t, void*) { return s3_fail(S3_ESTATE, "not implemented"); }
-int s3_index_finalize(s3_index*, void*) { return s3_fail(S3_ESTATE, "not implemented"); }
-int s3_index_csr(const s3_index*, int, const int32_t**, const int32_t**, int64_t*) { return s3_fail(S3_ESTATE, "not implemented"); }
-int s3_index_export(const s3_index*, int, int32_t*, int32_t*, void*) { return s3_fail(S3_ESTATE, "not implemented"); }
-int64_t s3_index_tokens(const s3_index*) { return 0; }
-size_t s3_index_build_workspace(int, int, int) { return 0; }
-int s3_index_build(const int32_t*, const int32_t*, int, int, int, int32_t*, int32_t*, void*, size_t, void*) { return s3_fail(S3_ESTATE, "not implemented"); }
-size_t s3_coactivate_score_workspace(const s3_index*, int64_t) { return 0; }
-int s3_coactivate_score(const s3_index*, const int32_t*, const float*, int, int64_t, int, int, int32_t, int, float*, int32_t*, float*, int32_t*, void*, size_t, void*) { return s3_fail(S3_ESTATE, "not implemented"); }
+
+#include <new>
+
+namespace {
+
+constexpr int kTilePost = 8192;       // postings per partition tile (upper bound)
+constexpr int kPartThreads = 256;
+constexpr int kSortThreads = 1024;
+constexpr int kSortCap = 16384;       // entries sorted per round in the bucket pass
+constexpr int kKeyRowBits = 13;       // tile-local key: bucket << 21 | f_lo << 13 | row_in_tile
+constexpr int kKeyBucketShift = 21;
+
+struct IdxDev {
+    uint32_t* inter;      // [n_heads][max_tiles * tile_post] packed (row << S | f_lo), bucket-sorted per tile
+    uint32_t* piece;      // [n_heads][NB][max_tiles]  (offset_in_tile << 16 | count)
+    int32_t* total;       // [n_heads][NB]
+    int32_t* bbase;       // [n_heads][NB + 1]
+    int32_t* offsets;     // [n_heads][n_feat + 1]  (stride off_stride)
+    int32_t* positions;   // [n_heads][pos_stride]
+    const int32_t* pos_log;   // [max_tokens] absolute position of each appended row
+    int64_t inter_stride, piece_stride, off_stride, pos_stride;
+    int n_feat, k, S, NB, nbB, ptok, tile_post, max_tiles;
+};
+
+__device__ __forceinline__ int padi(int i) { return i + (i >> 5); }
+
+// Exclusive prefix sum of one int per thread over the block, in thread order.
+template <int NT>
+__device__ __forceinline__ int block_excl_scan(int v, int* wsum, int& total) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    int x = v;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+        int y = __shfl_up(x, o);
+        if (lane >= o) x += y;
+    }
+    if (lane == 63) wsum[wave] = x;
+    __syncthreads();
+    int base = 0, tot = 0;
+#pragma unroll
+    for (int w = 0; w < NT / 64; ++w) {
+        int s = wsum[w];
+        if (w < wave) base += s;
+        tot += s;
+    }
+    __syncthreads();
+    total = tot;
+    return base + x - v;
 }
+
+// Stable LSD sort of the NT * E words in `a` (padded indexing) on key bits [bit_lo, bit_lo + nbits),
+// one bit per pass.  Thread t owns words [t E, (t + 1) E); ranks are prefix sums in that order.
+// Returns the buffer that holds the result.  Slots past the real entries must hold 0xFFFFFFFF.
+template <int NT>
+__device__ uint32_t* bitsplit_sort(uint32_t* a, uint32_t* b, int E, int bit_lo, int nbits, int* wsum) {
+    const int start = threadIdx.x * E;
+    for (int bit = bit_lo; bit < bit_lo + nbits; ++bit) {
+        int z = 0;
+        for (int i = 0; i < E; ++i) z += ((a[padi(start + i)] >> bit) & 1u) ? 0 : 1;
+        int tz;
+        int rz = block_excl_scan<NT>(z, wsum, tz);
+        int ro = tz + (start - rz);
+        for (int i = 0; i < E; ++i) {
+            uint32_t key = a[padi(start + i)];
+            int d = ((key >> bit) & 1u) ? ro++ : rz++;
+            b[padi(d)] = key;
+        }
+        __syncthreads();
+        uint32_t* t = a; a = b; b = t;
+    }
+    return a;
+}
+
+// One tile of <= tile_post postings of one head: sort by bucket, write the tile and its piece table.
+// `src` is the first row of tile `tile0` (row stride k, head stride head_stride elements).
+__global__ __launch_bounds__(kPartThreads) void idx_partition_kernel(const int32_t* src, int64_t head_stride,
+                                                                     int rows_avail, int tile0, IdxDev d) {
+    __shared__ uint32_t bufa[kTilePost + kTilePost / 32 + 8];
+    __shared__ uint32_t bufb[kTilePost + kTilePost / 32 + 8];
+    __shared__ int wsum[kPartThreads / 64];
+    __shared__ int bstart[256], bend[256];
+
+    const int tid = threadIdx.x, head = blockIdx.y;
+    const int tile = tile0 + blockIdx.x;
+    const int nrows = min(d.ptok, rows_avail - (int)blockIdx.x * d.ptok);
+    const int n = nrows * d.k;
+    const int32_t* s = src + (size_t)head * head_stride + (size_t)blockIdx.x * d.ptok * d.k;
+    const int E = (n + kPartThreads - 1) / kPartThreads;
+    const uint32_t mask = (1u << d.S) - 1u;
+
+    for (int i = tid; i < E * kPartThreads; i += kPartThreads) {
+        uint32_t key = 0xFFFFFFFFu;
+        if (i < n) {
+            uint32_t id = (uint32_t)s[i];
+            key = ((id >> d.S) << kKeyBucketShift) | ((id & mask) << kKeyRowBits) | (uint32_t)(i / d.k);
+        }
+        bufa[padi(i)] = key;
+    }
+    if (tid < 256) { bstart[tid] = 0; bend[tid] = 0; }
+    __syncthreads();
+    uint32_t* sorted = bitsplit_sort<kPartThreads>(bufa, bufb, E, kKeyBucketShift, d.nbB, wsum);
+
+    uint32_t* out = d.inter + (size_t)head * d.inter_stride + (size_t)tile * d.tile_post;
+    const uint32_t row0 = (uint32_t)tile * (uint32_t)d.ptok;
+    for (int i = tid; i < n; i += kPartThreads) {
+        uint32_t key = sorted[padi(i)];
+        int bk = (int)(key >> kKeyBucketShift);
+        int prev = i > 0 ? (int)(sorted[padi(i - 1)] >> kKeyBucketShift) : -1;
+        if (bk != prev) {
+            bstart[bk] = i;
+            if (prev >= 0) bend[prev] = i;
+        }
+        if (i == n - 1) bend[bk] = n;
+        out[i] = ((row0 + (key & ((1u << kKeyRowBits) - 1u))) << d.S) | ((key >> kKeyRowBits) & mask);
+    }
+    __syncthreads();
+    uint32_t* pc = d.piece + (size_t)head * d.piece_stride;
+    for (int b = tid; b < d.NB; b += kPartThreads)
+        pc[(size_t)b * d.max_tiles + tile] = ((uint32_t)bstart[b] << 16) | (uint32_t)(bend[b] - bstart[b]);
+}
+
+__global__ __launch_bounds__(256) void idx_totals_kernel(IdxDev d, int n_tiles) {
+    __shared__ int wsum[4];
+    const int b = blockIdx.x, head = blockIdx.y;
+    const uint32_t* pc = d.piece + (size_t)head * d.piece_stride + (size_t)b * d.max_tiles;
+    int acc = 0;
+    for (int t = threadIdx.x; t < n_tiles; t += 256) acc += (int)(pc[t] & 0xFFFFu);
+    int tot;
+    block_excl_scan<256>(acc, wsum, tot);
+    if (threadIdx.x == 0) d.total[(size_t)head * d.NB + b] = tot;
+}
+
+__global__ __launch_bounds__(256) void idx_bucket_scan_kernel(IdxDev d) {
+    __shared__ int wsum[4];
+    const int head = blockIdx.x, b = threadIdx.x;
+    int v = b < d.NB ? d.total[(size_t)head * d.NB + b] : 0;
+    int tot;
+    int ex = block_excl_scan<256>(v, wsum, tot);
+    int32_t* bb = d.bbase + (size_t)head * (d.NB + 1);
+    if (b < d.NB) bb[b] = ex;
+    if (b == 0) {
+        bb[d.NB] = tot;
+        d.offsets[(size_t)head * d.off_stride + d.n_feat] = tot;
+    }
+}
+
+// One (head, bucket): gather its pieces in tile order, sort by the low feature bits, write the CSR.
+__global__ __launch_bounds__(kSortThreads) void idx_bucket_sort_kernel(IdxDev d, int n_tiles) {
+    extern __shared__ __align__(16) uint32_t dyn[];
+    constexpr int kBuf = kSortCap + kSortCap / 32 + 8;
+    uint32_t* bufa = dyn;
+    uint32_t* bufb = dyn + kBuf;
+    int* pref = (int*)(dyn + 2 * kBuf);          // [kSortThreads + 1]
+    uint32_t* pinfo = (uint32_t*)(pref + kSortThreads + 1);   // [kSortThreads]
+    int* wsum = (int*)(pinfo + kSortThreads);     // [16]
+    int* hist = wsum + 16;                        // [256]
+    int* cursor = hist + 256;                     // [256]
+    int* rstart = cursor + 256;                   // [256]
+    int* rend = rstart + 256;                     // [256]
+
+    const int tid = threadIdx.x, b = blockIdx.x, head = blockIdx.y;
+    const int n_b = d.total[(size_t)head * d.NB + b];
+    const int out_base = d.bbase[(size_t)head * (d.NB + 1) + b];
+    const int nfl = min(1 << d.S, d.n_feat - (b << d.S));
+    const uint32_t mask = (1u << d.S) - 1u;
+    int32_t* offs = d.offsets + (size_t)head * d.off_stride + ((size_t)b << d.S);
+    if (n_b == 0) {
+        if (tid < nfl) offs[tid] = out_base;
+        return;
+    }
+    const uint32_t* pc = d.piece + (size_t)head * d.piece_stride + (size_t)b * d.max_tiles;
+    const uint32_t* inter = d.inter + (size_t)head * d.inter_stride;
+    int32_t* posout = d.positions + (size_t)head * d.pos_stride;
+    const bool multi = n_b > kSortCap;
+    const int lane = tid & 63, wave = tid >> 6;
+
+    if (tid < 256) hist[tid] = 0;
+    __syncthreads();
+    if (multi) {   // count the whole bucket first: the CSR offsets are needed before the first round is written
+        for (int t = wave; t < n_tiles; t += kSortThreads / 64) {
+            uint32_t p = pc[t];
+            int cnt = (int)(p & 0xFFFFu);
+            const uint32_t* e = inter + (size_t)t * d.tile_post + (p >> 16);
+            for (int i = lane; i < cnt; i += 64) atomicAdd(&hist[e[i] & mask], 1);
+        }
+        __syncthreads();
+        int tot;
+        int ex = block_excl_scan<kSortThreads>(tid < 256 ? hist[tid] : 0, wsum, tot);
+        if (tid < 256) cursor[tid] = out_base + ex;
+        if (tid < nfl) offs[tid] = out_base + ex;
+        __syncthreads();
+    }
+
+    for (int tp = 0; tp < n_tiles;) {
+        // take as many whole pieces (in tile order) as fit in one round
+        const int t = tp + tid;
+        uint32_t p = t < n_tiles ? pc[t] : 0u;
+        int cnt = (int)(p & 0xFFFFu);
+        int tot;
+        int ex = block_excl_scan<kSortThreads>(cnt, wsum, tot);
+        pref[tid] = ex;
+        pinfo[tid] = p;
+        if (tid == kSortThreads - 1) pref[kSortThreads] = tot;
+        int m = __syncthreads_count(ex + cnt <= kSortCap);
+        m = min(m, n_tiles - tp);
+        const int n_r = pref[m];
+        const int E = (n_r + kSortThreads - 1) / kSortThreads;
+
+        for (int i = tid; i < E * kSortThreads; i += kSortThreads) {
+            uint32_t e = 0xFFFFFFFFu;
+            if (i < n_r) {
+                int lo = 0, hi = m;                 // largest j with pref[j] <= i  (pref[m] = n_r > i)
+                while (hi - lo > 1) {
+                    int mid = (lo + hi) >> 1;
+                    if (pref[mid] <= i) lo = mid; else hi = mid;
+                }
+                e = inter[(size_t)(tp + lo) * d.tile_post + (pinfo[lo] >> 16) + (i - pref[lo])];
+                if (!multi) atomicAdd(&hist[e & mask], 1);
+            }
+            bufa[padi(i)] = e;
+        }
+        if (tid < 256) { rstart[tid] = 0; rend[tid] = 0; }
+        __syncthreads();
+        if (!multi) {
+            int tot2;
+            int ex2 = block_excl_scan<kSortThreads>(tid < 256 ? hist[tid] : 0, wsum, tot2);
+            if (tid < 256) cursor[tid] = out_base + ex2;
+            if (tid < nfl) offs[tid] = out_base + ex2;
+            __syncthreads();
+        }
+        uint32_t* sorted = bitsplit_sort<kSortThreads>(bufa, bufb, E, 0, d.S, wsum);
+        for (int i = tid; i < n_r; i += kSortThreads) {
+            int fl = (int)(sorted[padi(i)] & mask);
+            int prev = i > 0 ? (int)(sorted[padi(i - 1)] & mask) : -1;
+            if (fl != prev) {
+                rstart[fl] = i;
+                if (prev >= 0) rend[prev] = i;
+            }
+            if (i == n_r - 1) rend[fl] = n_r;
+        }
+        __syncthreads();
+        for (int i = tid; i < n_r; i += kSortThreads) {
+            uint32_t e = sorted[padi(i)];
+            int fl = (int)(e & mask);
+            posout[cursor[fl] + (i - rstart[fl])] = d.pos_log[e >> d.S];
+        }
+        __syncthreads();
+        if (tid < 256) cursor[tid] += rend[tid] - rstart[tid];
+        tp += m;
+        __syncthreads();
+    }
+}
+
+__global__ void idx_fill_positions_kernel(int32_t* dst, int n, int32_t base) {
+    int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) dst[i] = base + i;
+}
+
+size_t bucket_sort_lds() {
+    constexpr int kBuf = kSortCap + kSortCap / 32 + 8;
+    return (size_t)2 * kBuf * 4 + (kSortThreads + 1) * 4 + kSortThreads * 4 + 16 * 4 + 4 * 256 * 4;
+}
+
+struct Geometry {
+    int S, NB, nbB, ptok, tile_post;
+};
+
+bool geometry(int n_feat, int k, Geometry& g) {
+    if (n_feat < 1 || n_feat > S3_MAX_FEAT || k < 1 || k > S3_MAX_K) return false;
+    int bits = s3_ceil_log2((unsigned)n_feat);
+    g.S = bits > 8 ? bits - 8 : 0;
+    g.NB = (n_feat + (1 << g.S) - 1) >> g.S;
+    g.nbB = s3_ceil_log2((unsigned)g.NB);
+    g.ptok = kTilePost / k;
+    g.tile_post = g.ptok * k;
+    return true;
+}
+
+int run_partition(const int32_t* src, int64_t head_stride, int rows, int tile0, int n_heads, const IdxDev& d,
+                  hipStream_t st) {
+    if (rows <= 0) return S3_OK;
+    int ntiles = (rows + d.ptok - 1) / d.ptok;
+    hipLaunchKernelGGL(idx_partition_kernel, dim3(ntiles, n_heads), dim3(kPartThreads), 0, st, src, head_stride, rows,
+                       tile0, d);
+    S3_HIP(hipGetLastError());
+    return S3_OK;
+}
+
+int run_finalize(const IdxDev& d, int n_heads, int n_tiles, hipStream_t st) {
+    static bool attr_set = false;
+    if (!attr_set) {
+        S3_HIP(hipFuncSetAttribute((const void*)idx_bucket_sort_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                   (int)bucket_sort_lds()));
+        attr_set = true;
+    }
+    hipLaunchKernelGGL(idx_totals_kernel, dim3(d.NB, n_heads), dim3(256), 0, st, d, n_tiles);
+    hipLaunchKernelGGL(idx_bucket_scan_kernel, dim3(n_heads), dim3(256), 0, st, d);
+    hipLaunchKernelGGL(idx_bucket_sort_kernel, dim3(d.NB, n_heads), dim3(kSortThreads), bucket_sort_lds(), st, d,
+                       n_tiles);
+    S3_HIP(hipGetLastError());
+    return S3_OK;
+}
+
+}  // namespace
+
+struct s3_index {
+    int n_heads, n_feat, k;
+    int64_t max_tokens, tokens;
+    bool finalized;
+    Geometry g;
+    IdxDev d;
+    int32_t* pos_log;
+    int32_t* pending;     // [n_heads][ptok][k]: rows of the tile that is not complete yet
+    void* block;          // the one device allocation everything above lives in
+};
+
+// Internal view for the scoring translation unit.
+void s3_index_view(const s3_index* idx, int* n_heads, int* n_feat, int* k, int64_t* tokens,
+                                const int32_t** offsets, int64_t* off_stride, const int32_t** positions,
+                                int64_t* pos_stride, bool* finalized) {
+    *n_heads = idx->n_heads; *n_feat = idx->n_feat; *k = idx->k; *tokens = idx->tokens;
+    *offsets = idx->d.offsets; *off_stride = idx->d.off_stride;
+    *positions = idx->d.positions; *pos_stride = idx->d.pos_stride; *finalized = idx->finalized;
+}
+
+extern "C" {
+
+int s3_index_create(int n_heads, int n_feat, int k, int64_t max_tokens, s3_index** out) {
+    if (!out) return s3_fail(S3_EINVAL, "s3_index_create: null out");
+    Geometry g;
+    if (n_heads < 1 || !geometry(n_feat, k, g))
+        return s3_fail(S3_EINVAL, "s3_index_create: n_heads %d, n_feat %d (<= %d), k %d (<= %d) out of range", n_heads,
+                       n_feat, S3_MAX_FEAT, k, S3_MAX_K);
+    if (max_tokens < 1 || max_tokens > (1 << 24) || max_tokens * k >= (1LL << 31))
+        return s3_fail(S3_EINVAL, "s3_index_create: max_tokens %lld out of range (<= 2^24 and max_tokens * k < 2^31)",
+                       (long long)max_tokens);
+    s3_index* ix = new (std::nothrow) s3_index();
+    if (!ix) return s3_fail(S3_EHIP, "s3_index_create: out of host memory");
+    ix->n_heads = n_heads; ix->n_feat = n_feat; ix->k = k; ix->max_tokens = max_tokens; ix->tokens = 0;
+    ix->finalized = false; ix->g = g;
+    IdxDev& d = ix->d;
+    d.n_feat = n_feat; d.k = k; d.S = g.S; d.NB = g.NB; d.nbB = g.nbB; d.ptok = g.ptok; d.tile_post = g.tile_post;
+    d.max_tiles = (int)((max_tokens + g.ptok - 1) / g.ptok);
+    d.inter_stride = (int64_t)d.max_tiles * g.tile_post;
+    d.piece_stride = (int64_t)g.NB * d.max_tiles;
+    d.off_stride = n_feat + 1;
+    d.pos_stride = max_tokens * k;
+    size_t o = 0;
+    auto take = [&](size_t bytes) { size_t at = o; o += s3_align(bytes); return at; };
+    size_t o_inter = take((size_t)n_heads * d.inter_stride * 4);
+    size_t o_piece = take((size_t)n_heads * d.piece_stride * 4);
+    size_t o_total = take((size_t)n_heads * g.NB * 4);
+    size_t o_bbase = take((size_t)n_heads * (g.NB + 1) * 4);
+    size_t o_offs = take((size_t)n_heads * d.off_stride * 4);
+    size_t o_pos = take((size_t)n_heads * d.pos_stride * 4);
+    size_t o_plog = take((size_t)max_tokens * 4);
+    size_t o_pend = take((size_t)n_heads * g.tile_post * 4);
+    hipError_t e = hipMalloc(&ix->block, o);
+    if (e != hipSuccess) {
+        delete ix;
+        return s3_fail(S3_EHIP, "s3_index_create: hipMalloc of %zu bytes failed: %s", o, hipGetErrorString(e));
+    }
+    char* base = (char*)ix->block;
+    d.inter = (uint32_t*)(base + o_inter); d.piece = (uint32_t*)(base + o_piece);
+    d.total = (int32_t*)(base + o_total); d.bbase = (int32_t*)(base + o_bbase);
+    d.offsets = (int32_t*)(base + o_offs); d.positions = (int32_t*)(base + o_pos);
+    ix->pos_log = (int32_t*)(base + o_plog); d.pos_log = ix->pos_log;
+    ix->pending = (int32_t*)(base + o_pend);
+    *out = ix;
+    return S3_OK;
+}
+
+void s3_index_destroy(s3_index* idx) {
+    if (!idx) return;
+    if (idx->block) (void)hipFree(idx->block);
+    delete idx;
+}
+
+int64_t s3_index_tokens(const s3_index* idx) { return idx ? idx->tokens : 0; }
+
+int s3_index_append(s3_index* idx, const int32_t* ids, int T, const int32_t* positions, int32_t base_pos,
+                    void* stream) {
+    if (!idx || (!ids && T > 0)) return s3_fail(S3_EINVAL, "s3_index_append: null pointer");
+    if (T < 0) return s3_fail(S3_EINVAL, "s3_index_append: T %d < 0", T);
+    if (idx->finalized) return s3_fail(S3_ESTATE, "s3_index_append: index already finalized");
+    if (idx->tokens + T > idx->max_tokens)
+        return s3_fail(S3_ECAPACITY, "s3_index_append: %lld + %d tokens exceed max_tokens %lld", (long long)idx->tokens,
+                       T, (long long)idx->max_tokens);
+    if (T == 0) return S3_OK;
+    hipStream_t st = (hipStream_t)stream;
+    const IdxDev& d = idx->d;
+    const int k = idx->k, ptok = d.ptok, H = idx->n_heads;
+    const int64_t r0 = idx->tokens;
+    if (positions) {
+        S3_HIP(hipMemcpyAsync(idx->pos_log + r0, positions, (size_t)T * 4, hipMemcpyDeviceToDevice, st));
+    } else {
+        hipLaunchKernelGGL(idx_fill_positions_kernel, dim3((T + 255) / 256), dim3(256), 0, st, idx->pos_log + r0, T,
+                           base_pos);
+    }
+    int done = 0;
+    const int in_tile = (int)(r0 % ptok);
+    if (in_tile) {   // complete the tile left open by the previous append
+        int fill = T < ptok - in_tile ? T : ptok - in_tile;
+        S3_HIP(hipMemcpy2DAsync(idx->pending + (size_t)in_tile * k, (size_t)d.tile_post * 4, ids, (size_t)T * k * 4,
+                                (size_t)fill * k * 4, H, hipMemcpyDeviceToDevice, st));
+        done = fill;
+        if (in_tile + fill == ptok) {
+            int rc = run_partition(idx->pending, d.tile_post, ptok, (int)(r0 / ptok), H, d, st);
+            if (rc) return rc;
+        }
+    }
+    const int full = (T - done) / ptok * ptok;
+    if (full) {
+        int rc = run_partition(ids + (size_t)done * k, (int64_t)T * k, full, (int)((r0 + done) / ptok), H, d, st);
+        if (rc) return rc;
+        done += full;
+    }
+    if (done < T)   // rows of a tile that is not complete yet
+        S3_HIP(hipMemcpy2DAsync(idx->pending, (size_t)d.tile_post * 4, ids + (size_t)done * k, (size_t)T * k * 4,
+                                (size_t)(T - done) * k * 4, H, hipMemcpyDeviceToDevice, st));
+    idx->tokens += T;
+    return S3_OK;
+}
+
+int s3_index_finalize(s3_index* idx, void* stream) {
+    if (!idx) return s3_fail(S3_EINVAL, "s3_index_finalize: null index");
+    if (idx->finalized) return s3_fail(S3_ESTATE, "s3_index_finalize: already finalized");
+    hipStream_t st = (hipStream_t)stream;
+    const IdxDev& d = idx->d;
+    const int rem = (int)(idx->tokens % d.ptok);
+    if (rem) {
+        int rc = run_partition(idx->pending, d.tile_post, rem, (int)(idx->tokens / d.ptok), idx->n_heads, d, st);
+        if (rc) return rc;
+    }
+    const int n_tiles = (int)((idx->tokens + d.ptok - 1) / d.ptok);
+    int rc = run_finalize(d, idx->n_heads, n_tiles, st);
+    if (rc) return rc;
+    idx->finalized = true;
+    return S3_OK;
+}
+
+int s3_index_csr(const s3_index* idx, int head, const int32_t** offsets, const int32_t** positions,
+                 int64_t* n_postings) {
+    if (!idx || !offsets || !positions || !n_postings) return s3_fail(S3_EINVAL, "s3_index_csr: null pointer");
+    if (head < 0 || head >= idx->n_heads) return s3_fail(S3_EINVAL, "s3_index_csr: head %d out of range", head);
+    if (!idx->finalized) return s3_fail(S3_ESTATE, "s3_index_csr: index not finalized");
+    *offsets = idx->d.offsets + (size_t)head * idx->d.off_stride;
+    *positions = idx->d.positions + (size_t)head * idx->d.pos_stride;
+    *n_postings = idx->tokens * idx->k;
+    return S3_OK;
+}
+
+int s3_index_export(const s3_index* idx, int head, int32_t* offsets_out, int32_t* positions_out, void* stream) {
+    const int32_t *o, *p;
+    int64_t n;
+    int rc = s3_index_csr(idx, head, &o, &p, &n);
+    if (rc) return rc;
+    hipStream_t st = (hipStream_t)stream;
+    if (offsets_out)
+        S3_HIP(hipMemcpyAsync(offsets_out, o, (size_t)(idx->n_feat + 1) * 4, hipMemcpyDeviceToDevice, st));
+    if (positions_out && n)
+        S3_HIP(hipMemcpyAsync(positions_out, p, (size_t)n * 4, hipMemcpyDeviceToDevice, st));
+    return S3_OK;
+}
+
+// Workspace of the one-shot build: inter | piece | total | bbase | pos_log
+static size_t build_layout(int T, int k, int n_feat, const Geometry& g, size_t off[5]) {
+    int max_tiles = (T + g.ptok - 1) / g.ptok;
+    if (max_tiles < 1) max_tiles = 1;
+    size_t o = 0;
+    auto take = [&](size_t bytes) { size_t at = o; o += s3_align(bytes); return at; };
+    off[0] = take((size_t)max_tiles * g.tile_post * 4);
+    off[1] = take((size_t)g.NB * max_tiles * 4);
+    off[2] = take((size_t)g.NB * 4);
+    off[3] = take((size_t)(g.NB + 1) * 4);
+    off[4] = take((size_t)(T > 0 ? T : 1) * 4);
+    return o;
+}
+
+size_t s3_index_build_workspace(int T, int k, int n_feat) {
+    Geometry g;
+    if (T < 0 || !geometry(n_feat, k, g)) return 0;
+    size_t off[5];
+    return build_layout(T, k, n_feat, g, off);
+}
+
+int s3_index_build(const int32_t* ids, const int32_t* positions, int T, int k, int n_feat, int32_t* offsets,
+                   int32_t* out_positions, void* ws, size_t ws_bytes, void* stream) {
+    Geometry g;
+    if (T < 0 || !geometry(n_feat, k, g))
+        return s3_fail(S3_EINVAL, "s3_index_build: T %d, n_feat %d, k %d out of range", T, n_feat, k);
+    if (!offsets || (T > 0 && (!ids || !out_positions || !ws))) return s3_fail(S3_EINVAL, "s3_index_build: null pointer");
+    if (T > (1 << 24) || (int64_t)T * k >= (1LL << 31)) return s3_fail(S3_EINVAL, "s3_index_build: T %d too large", T);
+    size_t off[5];
+    size_t need = build_layout(T, k, n_feat, g, off);
+    if (T > 0 && ws_bytes < need) return s3_fail(S3_ECAPACITY, "s3_index_build: workspace %zu < %zu bytes", ws_bytes, need);
+    if (T > 0 && ((uintptr_t)ws & 255)) return s3_fail(S3_EINVAL, "s3_index_build: workspace must be 256-byte aligned");
+    hipStream_t st = (hipStream_t)stream;
+    if (T == 0) {
+        S3_HIP(hipMemsetAsync(offsets, 0, (size_t)(n_feat + 1) * 4, st));
+        return S3_OK;
+    }
+    char* base = (char*)ws;
+    IdxDev d;
+    d.n_feat = n_feat; d.k = k; d.S = g.S; d.NB = g.NB; d.nbB = g.nbB; d.ptok = g.ptok; d.tile_post = g.tile_post;
+    d.max_tiles = (T + g.ptok - 1) / g.ptok;
+    d.inter = (uint32_t*)(base + off[0]); d.piece = (uint32_t*)(base + off[1]);
+    d.total = (int32_t*)(base + off[2]); d.bbase = (int32_t*)(base + off[3]);
+    int32_t* plog = (int32_t*)(base + off[4]);
+    d.pos_log = plog; d.offsets = offsets; d.positions = out_positions;
+    d.inter_stride = 0; d.piece_stride = 0; d.off_stride = 0; d.pos_stride = 0;
+    if (positions) {
+        S3_HIP(hipMemcpyAsync(plog, positions, (size_t)T * 4, hipMemcpyDeviceToDevice, st));
+    } else {
+        hipLaunchKernelGGL(idx_fill_positions_kernel, dim3((T + 255) / 256), dim3(256), 0, st, plog, T, 0);
+    }
+    int rc = run_partition(ids, 0, T, 0, 1, d, st);
+    if (rc) return rc;
+    return run_finalize(d, 1, d.max_tiles, st);
+}
+
+}  // extern "C"

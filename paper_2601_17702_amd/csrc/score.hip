@@ -1,0 +1,322 @@
+// Generation-time co-activation scoring (Sec. 3.5 scoring equation; App. D.2 / App. E weights;
+// Sec. 3.5 "Adaptive Granularity" read as box pooling + fixed-length spans with NMS).
+//
+//   1. query weights   qw[h][f] = IDF_h(f) * sum of the query activations that name f
+//   2. postings gather S[t] += qw[h][f] for every t in I_h[f], all heads into one S
+//   3. span pooling    W[s] = S[s] + ... + S[s + len - 1]
+//   4. Top-B           greedy best window, optional suppression of overlapping windows
+//
+// Every sum is carried in 64-bit fixed point (power-of-two scales derived on the device from the
+// largest query activation / largest weight), so additions commute exactly: the result does not
+// depend on the order in which wavefronts reach a position, run-to-run output is bit-identical,
+// and a window's score is exactly the sum of its members.  Values are rounded to fp32 once, on
+// output.
+#include "s3_common.h"
+
+#include <math.h>
+
+namespace {
+
+struct Scal {
+    unsigned int qmax_bits;          // bits of the largest query activation (>= 0)
+    unsigned int pad;
+    unsigned long long qwmax_bits;   // bits (as double) of the largest query weight
+};
+
+struct ScoreArgs {
+    const int32_t* qids;
+    const float* qvals;
+    const int32_t* offsets;
+    const int32_t* positions;
+    int64_t off_stride, pos_stride;
+    int n_heads, n_feat, k, nq;
+    int64_t L, nW;
+    int len, top_b, nms, hb;
+    int32_t max_freq;
+    Scal* sc;
+    unsigned long long* qacc;        // [n_heads * n_feat] fixed-point sums, then doubles (query weights)
+    unsigned long long* sfix;        // [L]
+    long long* wfix;                 // [nW]
+    unsigned char* dead;             // [nW]
+    long long* tmaxv;                // [ntile]
+    int* tmaxi;                      // [ntile]
+    int ntile;
+    float* scores_out;
+    int32_t* span_start;
+    float* span_score;
+    int32_t* n_found;
+};
+
+constexpr int kTileW = 1024;
+
+__device__ __forceinline__ int exp_q(const Scal* sc) {   // activations are scaled by 2^exp_q: < 2^40 each
+    float q = __uint_as_float(sc->qmax_bits);
+    if (!(q > 0.f)) return 0;
+    int e;
+    frexpf(q, &e);
+    return 40 - e;
+}
+
+__device__ __forceinline__ int exp_s(const Scal* sc, int hb) {   // weights are scaled by 2^exp_s: sums < 2^62
+    double w = __longlong_as_double((long long)sc->qwmax_bits);
+    if (!(w > 0.0)) return 0;
+    int e;
+    frexp(w, &e);
+    return 62 - hb - e;
+}
+
+__global__ void sc_zero_kernel(unsigned long long* p, size_t n) {
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) p[i] = 0ull;
+}
+
+__global__ __launch_bounds__(256) void sc_qmax_kernel(ScoreArgs a) {
+    const size_t n = (size_t)a.n_heads * a.nq * a.k;
+    unsigned int m = 0;
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (size_t)gridDim.x * 256)
+        m = max(m, __float_as_uint(fmaxf(a.qvals[i], 0.f)));
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) m = max(m, (unsigned int)__shfl_xor((int)m, o));
+    if ((threadIdx.x & 63) == 0 && m) atomicMax(&a.sc->qmax_bits, m);
+}
+
+__global__ __launch_bounds__(256) void sc_qacc_kernel(ScoreArgs a) {
+    const size_t per_head = (size_t)a.nq * a.k, n = per_head * a.n_heads;
+    const double scale = ldexp(1.0, exp_q(a.sc));
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (size_t)gridDim.x * 256) {
+        float v = fmaxf(a.qvals[i], 0.f);
+        unsigned int f = (unsigned int)a.qids[i];
+        if (v > 0.f && f < (unsigned int)a.n_feat) {
+            size_t h = i / per_head;
+            atomicAdd(&a.qacc[h * a.n_feat + f], (unsigned long long)llrint((double)v * scale));
+        }
+    }
+}
+
+// fixed-point sum -> query weight (double, stored in place); App. D.2 IDF with natural log
+__global__ __launch_bounds__(256) void sc_qw_kernel(ScoreArgs a) {
+    const size_t n = (size_t)a.n_heads * a.n_feat;
+    const double inv = ldexp(1.0, -exp_q(a.sc));
+    double mx = 0.0;
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (size_t)gridDim.x * 256) {
+        unsigned long long s = a.qacc[i];
+        double w = 0.0;
+        if (s) {
+            size_t h = i / a.n_feat, f = i - h * a.n_feat;
+            const int32_t* off = a.offsets + h * a.off_stride;
+            int freq = off[f + 1] - off[f];
+            if (freq > 0 && !(a.max_freq > 0 && freq > a.max_freq))
+                w = (double)s * inv / (log(1.0 + (double)freq) + 1.0);
+        }
+        a.qacc[i] = (unsigned long long)__double_as_longlong(w);
+        mx = fmax(mx, w);
+    }
+    unsigned long long mb = (unsigned long long)__double_as_longlong(mx);
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+        unsigned int lo = (unsigned int)__shfl_xor((int)(unsigned int)mb, o);
+        unsigned int hi = (unsigned int)__shfl_xor((int)(unsigned int)(mb >> 32), o);
+        unsigned long long other = ((unsigned long long)hi << 32) | lo;
+        mb = other > mb ? other : mb;
+    }
+    if ((threadIdx.x & 63) == 0 && mb) atomicMax(&a.sc->qwmax_bits, mb);
+}
+
+// one wavefront per posting list with a non-zero weight
+__global__ __launch_bounds__(256) void sc_scatter_kernel(ScoreArgs a) {
+    const size_t wid = (size_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (wid >= (size_t)a.n_heads * a.n_feat) return;
+    const double w = __longlong_as_double((long long)a.qacc[wid]);
+    if (!(w > 0.0)) return;
+    const unsigned long long wf = (unsigned long long)llrint(w * ldexp(1.0, exp_s(a.sc, a.hb)));
+    if (!wf) return;
+    const size_t h = wid / a.n_feat, f = wid - h * a.n_feat;
+    const int32_t* off = a.offsets + h * a.off_stride;
+    const int32_t* pos = a.positions + h * a.pos_stride;
+    const int b = off[f], e = off[f + 1];
+    for (int i = b + (threadIdx.x & 63); i < e; i += 64) {
+        unsigned int p = (unsigned int)pos[i];
+        if (p < (unsigned long long)a.L) atomicAdd(&a.sfix[p], wf);
+    }
+}
+
+constexpr int kRun = 32;   // consecutive windows per thread (sliding sum, exact in integers)
+
+__global__ __launch_bounds__(256) void sc_pool_kernel(ScoreArgs a) {
+    const double inv = ldexp(1.0, -exp_s(a.sc, a.hb));
+    if (a.scores_out)
+        for (int64_t t = (int64_t)blockIdx.x * 256 + threadIdx.x; t < a.L; t += (int64_t)gridDim.x * 256)
+            a.scores_out[t] = (float)((double)a.sfix[t] * inv);
+    for (int64_t s0 = ((int64_t)blockIdx.x * 256 + threadIdx.x) * kRun; s0 < a.nW; s0 += (int64_t)gridDim.x * 256 * kRun) {
+        unsigned long long acc = 0;
+        for (int t = 0; t < a.len; ++t) acc += a.sfix[s0 + t];
+        a.wfix[s0] = (long long)acc;
+        for (int j = 1; j < kRun && s0 + j < a.nW; ++j) {
+            acc += a.sfix[s0 + j + a.len - 1] - a.sfix[s0 + j - 1];
+            a.wfix[s0 + j] = (long long)acc;
+        }
+    }
+}
+
+// (value, index) argmax over the block: larger value wins, ties -> smaller index; value -1 = nothing
+template <int NT>
+__device__ __forceinline__ void block_argmax(long long& v, int& i, long long* sv, int* si) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+        unsigned int lo = (unsigned int)__shfl_xor((int)(unsigned int)(unsigned long long)v, o);
+        unsigned int hi = (unsigned int)__shfl_xor((int)(unsigned int)((unsigned long long)v >> 32), o);
+        long long ov = (long long)(((unsigned long long)hi << 32) | lo);
+        int oi = __shfl_xor(i, o);
+        if (ov > v || (ov == v && oi < i)) { v = ov; i = oi; }
+    }
+    const int wave = threadIdx.x >> 6;
+    __syncthreads();
+    if ((threadIdx.x & 63) == 0) { sv[wave] = v; si[wave] = i; }
+    __syncthreads();
+    long long bv = sv[0];
+    int bi = si[0];
+#pragma unroll
+    for (int w = 1; w < NT / 64; ++w) {
+        long long ov = sv[w];
+        int oi = si[w];
+        if (ov > bv || (ov == bv && oi < bi)) { bv = ov; bi = oi; }
+    }
+    v = bv; i = bi;
+}
+
+__global__ __launch_bounds__(kTileW) void sc_tilemax_kernel(ScoreArgs a) {
+    __shared__ long long sv[kTileW / 64];
+    __shared__ int si[kTileW / 64];
+    const int64_t s = (int64_t)blockIdx.x * kTileW + threadIdx.x;
+    long long v = s < a.nW ? a.wfix[s] : -1;
+    int i = s < a.nW ? (int)s : 0x7FFFFFFF;
+    if (s < a.nW) a.dead[s] = 0;
+    block_argmax<kTileW>(v, i, sv, si);
+    if (threadIdx.x == 0) { a.tmaxv[blockIdx.x] = v; a.tmaxi[blockIdx.x] = i; }
+}
+
+__global__ __launch_bounds__(kTileW) void sc_topb_kernel(ScoreArgs a) {
+    __shared__ long long sv[kTileW / 64];
+    __shared__ int si[kTileW / 64];
+    const int tid = threadIdx.x;
+    const double inv = ldexp(1.0, -exp_s(a.sc, a.hb));
+    int found = 0;
+    for (int r = 0; r < a.top_b; ++r) {
+        long long v = -1;
+        int i = 0x7FFFFFFF;
+        for (int t = tid; t < a.ntile; t += kTileW) {
+            long long tv = a.tmaxv[t];
+            int ti = a.tmaxi[t];
+            if (tv > v || (tv == v && ti < i)) { v = tv; i = ti; }
+        }
+        block_argmax<kTileW>(v, i, sv, si);
+        if (v < 0) break;
+        if (tid == 0) {
+            a.span_start[r] = i;
+            a.span_score[r] = (float)((double)v * inv);
+        }
+        found = r + 1;
+        const int64_t lo = a.nms ? max((int64_t)0, (int64_t)i - a.len + 1) : i;
+        const int64_t hi = a.nms ? min(a.nW - 1, (int64_t)i + a.len - 1) : i;
+        for (int64_t s = lo + tid; s <= hi; s += kTileW) a.dead[s] = 1;
+        __syncthreads();
+        for (int t = (int)(lo / kTileW); t <= (int)(hi / kTileW); ++t) {
+            const int64_t s = (int64_t)t * kTileW + tid;
+            long long tv = (s < a.nW && !a.dead[s]) ? a.wfix[s] : -1;
+            int ti = tv >= 0 ? (int)s : 0x7FFFFFFF;
+            block_argmax<kTileW>(tv, ti, sv, si);
+            if (tid == 0) { a.tmaxv[t] = tv; a.tmaxi[t] = ti; }
+        }
+        __syncthreads();
+    }
+    for (int r = found + tid; r < a.top_b; r += kTileW) { a.span_start[r] = -1; a.span_score[r] = 0.f; }
+    if (tid == 0) a.n_found[0] = found;
+}
+
+struct Layout {
+    size_t sc, qacc, sfix, wfix, dead, tmaxv, tmaxi, total;
+};
+
+Layout layout(int n_heads, int n_feat, int64_t L) {
+    Layout l;
+    size_t o = 0;
+    auto take = [&](size_t bytes) { size_t at = o; o += s3_align(bytes); return at; };
+    const size_t ntile = (size_t)(L + kTileW - 1) / kTileW;
+    l.sc = take(sizeof(Scal));
+    l.sfix = take((size_t)L * 8);            // sc and sfix are adjacent: zeroed together with qacc
+    l.qacc = take((size_t)n_heads * n_feat * 8);
+    l.wfix = take((size_t)L * 8);
+    l.dead = take((size_t)L);
+    l.tmaxv = take(ntile * 8);
+    l.tmaxi = take(ntile * 4);
+    l.total = o;
+    return l;
+}
+
+}  // namespace
+
+extern "C" size_t s3_coactivate_score_workspace(const s3_index* idx, int64_t n_positions) {
+    if (!idx || n_positions < 1) return 0;
+    int n_heads, n_feat, k;
+    int64_t tokens, os, ps;
+    const int32_t *off, *pos;
+    bool fin;
+    s3_index_view(idx, &n_heads, &n_feat, &k, &tokens, &off, &os, &pos, &ps, &fin);
+    return layout(n_heads, n_feat, n_positions).total;
+}
+
+extern "C" int s3_coactivate_score(const s3_index* idx, const int32_t* qids, const float* qvals, int nq,
+                                   int64_t n_positions, int span_len, int top_b, int32_t max_freq, int nms,
+                                   float* scores_out, int32_t* span_start, float* span_score, int32_t* n_found,
+                                   void* ws, size_t ws_bytes, void* stream) {
+    if (!idx || !span_start || !span_score || !n_found || !ws) return s3_fail(S3_EINVAL, "s3_coactivate_score: null pointer");
+    if (nq < 0 || (nq > 0 && (!qids || !qvals))) return s3_fail(S3_EINVAL, "s3_coactivate_score: bad query arrays");
+    if (span_len < 1 || top_b < 1 || top_b > 1024)
+        return s3_fail(S3_EINVAL, "s3_coactivate_score: span_len %d (>= 1) / top_b %d (1..1024) out of range", span_len, top_b);
+    if (n_positions < 1 || n_positions >= (1LL << 31))
+        return s3_fail(S3_EINVAL, "s3_coactivate_score: n_positions %lld out of range", (long long)n_positions);
+    ScoreArgs a;
+    int64_t tokens;
+    bool fin;
+    s3_index_view(idx, &a.n_heads, &a.n_feat, &a.k, &tokens, &a.offsets, &a.off_stride, &a.positions, &a.pos_stride, &fin);
+    if (!fin) return s3_fail(S3_ESTATE, "s3_coactivate_score: index not finalized");
+    if ((int64_t)nq * a.k > (1 << 20)) return s3_fail(S3_EINVAL, "s3_coactivate_score: nq * k %lld > 2^20", (long long)nq * a.k);
+    const Layout l = layout(a.n_heads, a.n_feat, n_positions);
+    if (ws_bytes < l.total) return s3_fail(S3_ECAPACITY, "s3_coactivate_score: workspace %zu < %zu bytes", ws_bytes, l.total);
+    if ((uintptr_t)ws & 255) return s3_fail(S3_EINVAL, "s3_coactivate_score: workspace must be 256-byte aligned");
+
+    char* base = (char*)ws;
+    a.qids = qids; a.qvals = qvals; a.nq = nq;
+    a.L = n_positions;
+    a.len = (int)(span_len < n_positions ? span_len : n_positions);
+    a.nW = n_positions - a.len + 1;
+    a.top_b = top_b; a.nms = nms ? 1 : 0; a.max_freq = max_freq;
+    a.hb = s3_ceil_log2((unsigned)(a.n_heads * a.k)) + 4;   // up to 16 x n_heads x k contributions per position
+    if (a.hb > 40) return s3_fail(S3_EINVAL, "s3_coactivate_score: n_heads * k too large");
+    a.sc = (Scal*)(base + l.sc);
+    a.sfix = (unsigned long long*)(base + l.sfix);
+    a.qacc = (unsigned long long*)(base + l.qacc);
+    a.wfix = (long long*)(base + l.wfix);
+    a.dead = (unsigned char*)(base + l.dead);
+    a.tmaxv = (long long*)(base + l.tmaxv);
+    a.tmaxi = (int*)(base + l.tmaxi);
+    a.ntile = (int)((a.nW + kTileW - 1) / kTileW);
+    a.scores_out = scores_out; a.span_start = span_start; a.span_score = span_score; a.n_found = n_found;
+
+    hipStream_t st = (hipStream_t)stream;
+    const size_t nzero = (l.wfix - l.sc) / 8;   // Scal + sfix + qacc
+    auto blocks = [](size_t n, size_t per) { size_t b = (n + per - 1) / per; return (unsigned)(b < 1 ? 1 : (b > 65536 ? 65536 : b)); };
+    hipLaunchKernelGGL(sc_zero_kernel, dim3(blocks(nzero, 256)), dim3(256), 0, st, (unsigned long long*)(base + l.sc), nzero);
+    const size_t npairs = (size_t)a.n_heads * nq * a.k;
+    if (npairs) {
+        hipLaunchKernelGGL(sc_qmax_kernel, dim3(blocks(npairs, 256 * 4)), dim3(256), 0, st, a);
+        hipLaunchKernelGGL(sc_qacc_kernel, dim3(blocks(npairs, 256)), dim3(256), 0, st, a);
+        const size_t nhf = (size_t)a.n_heads * a.n_feat;
+        hipLaunchKernelGGL(sc_qw_kernel, dim3(blocks(nhf, 256)), dim3(256), 0, st, a);
+        hipLaunchKernelGGL(sc_scatter_kernel, dim3((unsigned)((nhf + 3) / 4)), dim3(256), 0, st, a);
+    }
+    hipLaunchKernelGGL(sc_pool_kernel, dim3(blocks((size_t)a.L, 256)), dim3(256), 0, st, a);
+    hipLaunchKernelGGL(sc_tilemax_kernel, dim3(a.ntile), dim3(kTileW), 0, st, a);
+    hipLaunchKernelGGL(sc_topb_kernel, dim3(1), dim3(kTileW), 0, st, a);
+    S3_HIP(hipGetLastError());
+    return S3_OK;
+}

@@ -1,0 +1,50 @@
+"""CPU-only checks of the C-ABI library: it loads, exports every declared symbol, and rejects bad
+arguments on the host before anything touches a GPU."""
+import ctypes as C
+import os
+import re
+
+import paper_2601_17702_amd as s3
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "s3attn.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(s3_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    names = declared_symbols()
+    assert "s3_sae_encode_topk" in names and "s3_index_finalize" in names and "s3_coactivate_score" in names
+    lib = C.CDLL(s3.LIB_PATH)
+    for n in names:
+        assert hasattr(lib, n), f"{n} declared in include/s3attn.h but not exported"
+
+
+def test_host_side_argument_validation():
+    L = s3.lib()
+    one = C.c_void_p(256)           # non-null, never dereferenced: validation fails first
+    bad = [
+        L.s3_sae_encode_topk(None, 0, 8, 128, one, one, 64, 4, 1, one, one, None),        # null x
+        L.s3_sae_encode_topk(one, 2, 8, 128, one, one, 64, 4, 1, one, one, None),         # dtype
+        L.s3_sae_encode_topk(one, 0, 8, 96, one, one, 64, 4, 1, one, one, None),          # d_head
+        L.s3_sae_encode_topk(one, 0, 8, 128, one, one, 64, 65, 1, one, one, None),        # k > S3_MAX_K
+        L.s3_sae_encode_topk(one, 0, 8, 128, one, one, 16, 32, 1, one, one, None),        # k > n_feat
+        L.s3_sae_encode_topk(one, 0, 8, 128, one, one, 70000, 4, 1, one, one, None),      # n_feat
+        L.s3_sae_encode_topk(one, 0, -1, 128, one, one, 64, 4, 1, one, one, None),        # T
+        L.s3_sae_encode_topk(C.c_void_p(264), 0, 8, 128, one, one, 64, 4, 1, one, one, None),   # alignment
+    ]
+    assert all(rc == -1 for rc in bad)
+    assert b"s3_sae_encode_topk" in L.s3_last_error()
+    h = C.c_void_p()
+    assert L.s3_index_create(0, 64, 4, 10, C.byref(h)) == -1
+    assert L.s3_index_create(1, 64, 65, 10, C.byref(h)) == -1
+    assert L.s3_index_create(1, 64, 4, 1 << 25, C.byref(h)) == -1
+    assert L.s3_index_append(None, one, 1, None, 0, None) == -1
+    assert L.s3_index_finalize(None, None) == -1
+    assert L.s3_index_build(one, None, 8, 4, 64, one, one, one, 16, None) == -3          # workspace too small
+    assert L.s3_index_build_workspace(8, 4, 64) > 0 and L.s3_index_build_workspace(8, 65, 64) == 0
+    assert L.s3_coactivate_score(None, one, one, 1, 10, 4, 2, 0, 1, None, one, one, one, one, 1 << 20, None) == -1
+    assert s3.MAX_K == 64 and s3.MAX_FEAT == 65536
