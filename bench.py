@@ -1,0 +1,181 @@
+#!/usr/bin/env python3
+"""Benchmark of the S3-Attention hot path on one MI355X.
+
+One step = one pass of the whole path over one synthetic context: for every chunk
+sae_encode_topk -> index_append, then index_finalize, then the query encode and
+coactivate_score (position scores, span pooling, Top-B).  Inputs are resident in HBM before the
+timed region starts.  Prints ONE JSON line (see the design doc for the fields).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+from paper_2601_17702_amd import synth  # noqa: E402
+
+MFMA_PEAK_TFLOPS = {"bf16": 2500.0, "fp32": 157.3}   # MI355X dense matrix peaks
+
+
+def gen_inputs(w, torch, threads=16):
+    """All chunks of all heads, W_enc, b_enc and the queries, generated on the host and moved to HBM."""
+    from concurrent.futures import ThreadPoolExecutor
+    tdt = torch.bfloat16 if w.dtype == "bf16" else torch.float32
+    H, C = w.n_heads, w.n_chunks
+    assert w.L % w.T == 0
+    K = torch.empty((C, H, w.T, w.d_head), dtype=tdt, device="cuda")
+    W = torch.empty((H, w.n_feat, w.d_head), dtype=tdt, device="cuda")
+    B = torch.empty((H, w.n_feat), dtype=torch.float32, device="cuda")
+    Q = torch.empty((H, w.nq, w.d_head), dtype=tdt, device="cuda")
+
+    def as_t(a):
+        t = torch.from_numpy(a.view(np.int16) if a.dtype == np.uint16 else a)
+        return t.view(torch.bfloat16) if a.dtype == np.uint16 else t
+
+    def one_head(h):
+        return (h, [synth.gen_keys(w, h, c) for c in range(C)], synth.gen_w_enc(w, h), synth.gen_b_enc(w, h),
+                synth.gen_queries(w, h))
+
+    with ThreadPoolExecutor(max_workers=threads) as ex:
+        for h, ks, wh, bh, qh in ex.map(one_head, range(H)):
+            for c in range(C):
+                K[c, h].copy_(as_t(ks[c]))
+            W[h].copy_(as_t(wh))
+            B[h].copy_(torch.from_numpy(bh))
+            Q[h].copy_(as_t(qh))
+    torch.cuda.synchronize()
+    return K, W, B, Q
+
+
+def cpu_baseline(w, sample_tokens, sample_heads):
+    """The oracle, as it stands, on a bounded sample of the same workload (host cores, OpenMP over rows)."""
+    from oracle import s3_oracle as orc
+    sw = synth.shrink(w, L=sample_tokens, T=min(w.T, sample_tokens))
+    dt, S = 0.0, np.zeros(sample_tokens)
+    for h in range(sample_heads):
+        x = np.concatenate([synth.gen_keys(sw, h, c) for c in range(sw.n_chunks)])
+        W, b, q = synth.gen_w_enc(sw, h), synth.gen_b_enc(sw, h), synth.gen_queries(sw, h)
+        t0 = time.perf_counter()
+        enc = orc.encode_topk(x, W, b, w.k, w.dtype)
+        ix = orc.Index(w.n_feat)
+        ix.append(enc["ids"], np.arange(x.shape[0], dtype=np.int32))
+        ix.csr()
+        qe = orc.encode_topk(q, W, b, w.k, w.dtype)
+        ix.score_accumulate(qe["ids"], qe["vals"], S)
+        dt += time.perf_counter() - t0
+    t0 = time.perf_counter()
+    orc.topb(orc.pool(S, w.span_len), w.span_len, w.top_b, nms=True)
+    dt += time.perf_counter() - t0
+    return {"value": sample_heads * sample_tokens / dt, "unit": "tokens\u00b7heads/s", "cores": orc.threads(),
+            "kind": "oracle", "sample": f"{sample_heads} heads x {sample_tokens} tokens of {w.name} "
+            f"(encode+Top-k+index+score), {dt:.1f} s"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=3)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--workload", default="c2_llama8b", choices=sorted(synth.WORKLOADS))
+    ap.add_argument("--cpu-sample-tokens", type=int, default=0, help="0 = min(L, 32768)")
+    ap.add_argument("--cpu-sample-heads", type=int, default=3)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on ONE GPU (no collectives, no sharding); use --gpus 1")
+
+    import torch
+    import paper_2601_17702_amd as s3
+    s3.lib()                                   # fail loudly if the HIP library is not built
+    w = synth.WORKLOADS[args.workload]
+    H = w.n_heads
+    K, W, B, Q = gen_inputs(w, torch)
+    ids = torch.empty((H, w.T, w.k), dtype=torch.int32, device="cuda")
+    vals = torch.empty((H, w.T, w.k), dtype=torch.float32, device="cuda")
+    qids = torch.empty((H, w.nq, w.k), dtype=torch.int32, device="cuda")
+    qvals = torch.empty((H, w.nq, w.k), dtype=torch.float32, device="cuda")
+    index = s3.Index(H, w.n_feat, w.k, w.L)
+    ws = torch.empty(index.score_workspace(w.L), dtype=torch.uint8, device="cuda")
+    ev = lambda: torch.cuda.Event(enable_timing=True)  # noqa: E731
+
+    def step(timers=None):
+        index.reset()
+        marks = []
+        for c in range(w.n_chunks):
+            if timers is not None:
+                a, b, d = ev(), ev(), ev()
+                a.record()
+            s3.sae_encode_topk(K[c], W, B, w.k, ids, vals)
+            if timers is not None:
+                b.record()
+            index.append(ids, base_pos=c * w.T)
+            if timers is not None:
+                d.record()
+                marks.append((a, b, d))
+        f0, f1, f2, f3 = (ev(), ev(), ev(), ev()) if timers is not None else (None,) * 4
+        if timers is not None:
+            f0.record()
+        index.finalize()
+        if timers is not None:
+            f1.record()
+        s3.sae_encode_topk(Q, W, B, w.k, qids, qvals)
+        if timers is not None:
+            f2.record()
+        out = index.coactivate_score(qids, qvals, w.L, w.span_len, w.top_b, max_freq=0, nms=True, ws=ws)
+        if timers is not None:
+            f3.record()
+            timers.append((marks, f0, f1, f2, f3))
+        return out
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    timers = []
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        out = step(timers)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+
+    enc_ms = [a.elapsed_time(b) for marks, *_ in timers for a, b, _ in marks]
+    app_ms = [b.elapsed_time(d) for marks, *_ in timers for _, b, d in marks]
+    fin_ms = [f0.elapsed_time(f1) for _, f0, f1, _, _ in timers]
+    qenc_ms = [f1.elapsed_time(f2) for _, _, f1, f2, _ in timers]
+    score_ms = [f2.elapsed_time(f3) for _, _, _, f2, f3 in timers]
+    enc_avg = float(np.mean(enc_ms))
+    flop_per_launch = 2.0 * w.d_head * w.n_feat * w.T * H       # encoder GEMM of one chunk, all heads
+    achieved = flop_per_launch / (enc_avg * 1e-3) / 1e12
+    peak = MFMA_PEAK_TFLOPS[w.dtype]
+    ms_per_step = dt / args.steps * 1e3
+    res = {
+        "metric": "scanned tokens\u00b7heads/sec (encode+TopK+index) at Llama-8B shape; % MFMA/HBM peak",
+        "value": w.token_heads / (ms_per_step * 1e-3),
+        "unit": "tokens\u00b7heads/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": w.dtype, "data": "synthetic",
+        "config": {"workload": w.name, "layers": w.layers, "kv_heads": w.kv_heads, "tokens": w.L, "chunk": w.T,
+                   "d_head": w.d_head, "n_feat": w.n_feat, "k": w.k, "queries_per_kv_head": w.nq,
+                   "span_len": w.span_len, "top_b": w.top_b},
+        "stages_ms": {"encode_topk": float(np.sum(enc_ms)) / args.steps, "index_append": float(np.sum(app_ms)) / args.steps,
+                      "index_finalize": float(np.mean(fin_ms)), "query_encode": float(np.mean(qenc_ms)),
+                      "coactivate_score": float(np.mean(score_ms))},
+        "roofline": {"kernel": "sae_encode_topk_kernel", "bound": "mfma", "achieved": achieved, "peak": peak,
+                     "unit": "TFLOP/s", "frac": achieved / peak, "traffic": None,
+                     "launch_ms": enc_avg, "flop_per_launch": flop_per_launch},
+        "spans_found": int(out[2].item()),
+    }
+    if not args.no_cpu_baseline:
+        res["cpu_baseline"] = cpu_baseline(w, args.cpu_sample_tokens or min(w.L, 32768), args.cpu_sample_heads)
+    print(json.dumps(res))
+
+
+if __name__ == "__main__":
+    main()

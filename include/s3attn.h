@@ -100,6 +100,11 @@ int s3_index_csr(const s3_index* idx, int head, const int32_t** offsets,
 int s3_index_export(const s3_index* idx, int head, int32_t* offsets_out, int32_t* positions_out,
                     void* stream);
 
+/* Forget everything appended (tokens = 0, not finalized) and keep the allocations, so that the
+ * next context can be indexed without allocating (Alg. 1 "Initialize inverted index").  Work
+ * already queued on a stream keeps reading the old contents: order the reset after it. */
+int s3_index_reset(s3_index* idx);
+
 /* Tokens appended so far (host value). */
 int64_t s3_index_tokens(const s3_index* idx);
 

@@ -42,6 +42,8 @@ def lib():
         L.s3_index_csr.argtypes = [vp, ci, C.POINTER(vp), C.POINTER(vp), C.POINTER(i64)]
         L.s3_index_export.argtypes = [vp, ci, vp, vp, vp]
         L.s3_index_export.restype = ci
+        L.s3_index_reset.argtypes = [vp]
+        L.s3_index_reset.restype = ci
         L.s3_index_tokens.argtypes = [vp]
         L.s3_index_tokens.restype = i64
         L.s3_index_build_workspace.argtypes = [ci, ci, ci]
@@ -120,6 +122,9 @@ class Index:
 
     def finalize(self):
         _check(lib().s3_index_finalize(self._h, _stream()))
+
+    def reset(self):
+        _check(lib().s3_index_reset(self._h))
 
     @property
     def tokens(self) -> int:

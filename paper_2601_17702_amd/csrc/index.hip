@@ -397,6 +397,13 @@ void s3_index_destroy(s3_index* idx) {
 
 int64_t s3_index_tokens(const s3_index* idx) { return idx ? idx->tokens : 0; }
 
+int s3_index_reset(s3_index* idx) {
+    if (!idx) return s3_fail(S3_EINVAL, "s3_index_reset: null index");
+    idx->tokens = 0;
+    idx->finalized = false;
+    return S3_OK;
+}
+
 int s3_index_append(s3_index* idx, const int32_t* ids, int T, const int32_t* positions, int32_t base_pos,
                     void* stream) {
     if (!idx || (!ids && T > 0)) return s3_fail(S3_EINVAL, "s3_index_append: null pointer");
