@@ -36,15 +36,6 @@ constexpr int kTokWG = kWaves * kTokWave;
 constexpr int kFT = 32;           // features per tile (MFMA M)
 constexpr int kHeadroom = 32;     // free list slots required at the start of a tile (16 per lane)
 
-struct EncParams {
-    const char* x;
-    const char* w;
-    const float* b;
-    int32_t* ids;
-    float* vals;
-    int T, n_feat, k, capt, tiles_per_head;
-};
-
 __device__ __forceinline__ int wave_max_i(int v) {
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) v = max(v, __shfl_xor(v, o));
@@ -217,8 +208,8 @@ __global__ __launch_bounds__(kThreads) void sae_encode_topk_kernel(EncParams p) 
 
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
     const int n = lane & 31, half = lane >> 5;
-    const int head = blockIdx.x / p.tiles_per_head;
-    const int tt = blockIdx.x - head * p.tiles_per_head;
+    int head, tt;
+    s3_block_to_tile(blockIdx.x, p.n_heads, p.tiles_per_head, head, tt);
     const int tok = tt * kTokWG + wv * kTokWave + n;
     const bool tok_ok = tok < p.T;
 
@@ -235,7 +226,7 @@ __global__ __launch_bounds__(kThreads) void sae_encode_topk_kernel(EncParams p) 
     c.base = half ? (p.capt - 1) * 32 + n : n;
     c.step = half ? -32 : 32;
     int cnt = 0;
-    float tau = -INFINITY;
+    float tau = p.ablate ? INFINITY : -INFINITY;
     const int k = p.k;
     const int loose = k + (k >> 3) + 2;
 
@@ -337,11 +328,6 @@ __global__ __launch_bounds__(kThreads) void sae_encode_topk_kernel(EncParams p) 
     }
 }
 
-int env_int(const char* name, int dflt) {
-    const char* s = getenv(name);
-    return s && *s ? atoi(s) : dflt;
-}
-
 template <int DT, int DH>
 int launch(const EncParams& p, int n_heads, hipStream_t st) {
     using F = Frag<DT, DH>;
@@ -362,6 +348,11 @@ int launch(const EncParams& p, int n_heads, hipStream_t st) {
 
 }  // namespace
 
+int env_int(const char* name, int dflt) {
+    const char* s = getenv(name);
+    return s && *s ? atoi(s) : dflt;
+}
+
 extern "C" int s3_sae_encode_topk(const void* x, int dtype, int T, int d_head, const void* w_enc,
                                   const float* b_enc, int n_feat, int k, int n_heads, int32_t* ids,
                                   float* vals, void* stream) {
@@ -378,14 +369,16 @@ extern "C" int s3_sae_encode_topk(const void* x, int dtype, int T, int d_head, c
 
     EncParams p;
     p.x = (const char*)x; p.w = (const char*)w_enc; p.b = b_enc; p.ids = ids; p.vals = vals;
-    p.T = T; p.n_feat = n_feat; p.k = k;
+    p.T = T; p.n_feat = n_feat; p.k = k; p.n_heads = n_heads;
+    p.ablate = env_int("S3_ENC_ABLATE", 0);
+    hipStream_t st = (hipStream_t)stream;
+    if (dtype == S3_BF16 && k <= 32 && d_head <= 128 && env_int("S3_ENC_GENERIC", 0) == 0) return s3_encode_fast_launch(p, d_head, st);
     p.tiles_per_head = (T + kTokWG - 1) / kTokWG;
     // list capacity per token: k survivors + headroom for one tile + room for new candidates between refreshes
     int capt = k + kHeadroom + (k <= 32 ? 16 : 32);
     capt = env_int("S3_ENC_CAPT", capt);
     if (capt < k + kHeadroom + 4 || capt > 512) return s3_fail(S3_EINVAL, "s3_sae_encode_topk: bad S3_ENC_CAPT %d", capt);
     p.capt = capt;
-    hipStream_t st = (hipStream_t)stream;
 #define S3_CASE(DT, DH) if (dtype == DT && d_head == DH) return launch<DT, DH>(p, n_heads, st);
     S3_CASE(S3_BF16, 64) S3_CASE(S3_BF16, 128) S3_CASE(S3_BF16, 256)
     S3_CASE(S3_FP32, 64) S3_CASE(S3_FP32, 128) S3_CASE(S3_FP32, 256)

@@ -26,3 +26,32 @@ static inline int s3_ceil_log2(unsigned v) {
 void s3_index_view(const s3_index* idx, int* n_heads, int* n_feat, int* k, int64_t* tokens,
                    const int32_t** offsets, int64_t* off_stride, const int32_t** positions,
                    int64_t* pos_stride, bool* finalized);
+
+// ---- encoder internals shared by the generic and the fast kernel ----
+struct EncParams {
+    const char* x;
+    const char* w;
+    const float* b;
+    int32_t* ids;
+    float* vals;
+    int T, n_feat, k, n_heads, capt, tiles_per_head, ablate;
+};
+
+int env_int(const char* name, int dflt);
+int s3_encode_fast_launch(EncParams p, int d_head, hipStream_t st);   // bf16, k <= 32
+
+// Workgroup -> (head, token tile).  Workgroups are dealt round-robin to the 8 XCDs (each with its own
+// L2), so consecutive tiles of one head are placed on the SAME XCD: they stream the same W_enc rows at
+// about the same time and share them in that L2.  Heads beyond the last multiple of 8 map linearly.
+__device__ __forceinline__ void s3_block_to_tile(unsigned bid, int n_heads, int tiles_per_head, int& head, int& tt) {
+    const unsigned full = (unsigned)(n_heads / 8) * 8u * (unsigned)tiles_per_head;
+    if (bid < full) {
+        unsigned xcd = bid & 7u, slot = bid >> 3;
+        head = (int)(slot / tiles_per_head) * 8 + (int)xcd;
+        tt = (int)(slot % tiles_per_head);
+    } else {
+        unsigned r = bid - full;
+        head = (n_heads / 8) * 8 + (int)(r / tiles_per_head);
+        tt = (int)(r % tiles_per_head);
+    }
+}
