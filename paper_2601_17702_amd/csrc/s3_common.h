@@ -35,6 +35,10 @@ struct EncParams {
     int32_t* ids;
     float* vals;
     int T, n_feat, k, n_heads, capt, tiles_per_head, ablate;
+    float opt_c;   // fast path: optimistic start tau0 = mean + opt_c * std (<= 0: start from -inf)
+    int soft;      // fast path: list length per lane that asks for a workgroup-wide refresh (0: off)
+    int skew;      // fast path: 1 = odd wavefronts run half a stage late, 0 = wavefronts 4-7
+    unsigned long long* dbg;   // optional device counters for tuning (null in normal use)
 };
 
 int env_int(const char* name, int dflt);
