@@ -5,6 +5,7 @@
 //
 //   - workgroup = 8 wavefronts = 256 tokens; a stage of 64 features (two 32x32 MFMA tiles per
 //     wavefront) is staged once per workgroup through LDS, double-buffered, one barrier per stage;
+//     global loads run two stages ahead in two alternating register sets;
 //   - b_enc rides in the GEMM: each staged W row carries the bias split exactly into three bf16
 //     terms in its 16-byte pad, multiplied by a constant [1, 1, 1, 0...] operand in a ninth K step,
 //     so accumulators start from the literal 0 and no bias is read or added by the vector ALU;
@@ -14,10 +15,6 @@
 //   - the epilogue tests 4 accumulators per uniform branch; each lane owns a fixed list of CAPL
 //     slots, so "list nearly full" is one compare on the lane's write pointer after a group that
 //     appended;
-//   - optimistic start: tau begins at mean + c * std of the token's first 64 pre-activations instead
-//     of -inf.  This is only a guess: a token is accepted iff at least k of its pre-activations
-//     exceeded tau (then nothing that was dropped can belong to its Top-k); if any token of the
-//     workgroup fails the test, the workgroup runs again from tau = -inf;
 //   - threshold refreshes are voted per workgroup at the stage barrier, so that all wavefronts
 //     refresh in the same stage instead of stalling each other one after the other; the refresh
 //     loads the lane's candidates into registers once and narrows tau there;
@@ -43,6 +40,10 @@ constexpr int kGuard = 4;        // appends possible between two fullness checks
 constexpr int ES = 2;
 typedef __attribute__((address_space(3))) float lds_f32;
 typedef __attribute__((address_space(3))) uint16_t lds_u16;
+typedef __attribute__((address_space(3))) int lds_i32;
+
+// compile-time ablation masks of the tuning builds (0 in the product kernel)
+constexpr int kNoHits = 1, kNoLoads = 2, kNoEpilogue = 4, kNoMfma = 8;
 
 __device__ __forceinline__ unsigned ordered_key(float v) {
     unsigned u = __float_as_uint(v);
@@ -76,13 +77,15 @@ struct Refreshed {
 // dropped candidate is below k kept ones (ties: higher feature id).  Counts are over both lanes of
 // the token.  The search for tau brackets the k-th largest value between lo (count >= k) and hi
 // (count < k) and alternates interpolation on the counts with plain halving.
-__device__ __noinline__ Refreshed refresh_fast(List L, int k, int target, int cnt, float tau, unsigned long long* dbg) {
+__device__ __noinline__ Refreshed refresh_fast(List L, int k, int target, int cnt, float tau) {
     const int total = cnt + __shfl_xor(cnt, 32);
     const bool active = total >= k;
     float r[CAPL];
+    uint16_t ids[CAPL];
 #pragma unroll
     for (int i = 0; i < CAPL; ++i) {
         float v = L.cv[32 * i];
+        ids[i] = L.ci[32 * i];
         r[i] = i < cnt ? v : -INFINITY;
     }
     float mx = -INFINITY;
@@ -120,7 +123,6 @@ __device__ __noinline__ Refreshed refresh_fast(List L, int k, int target, int cn
             else { hi = mid; chi = cm; }
         }
         interp = !interp;
-        if (dbg && (threadIdx.x & 63) == 0) atomicAdd(&dbg[5], 1ull);
     }
     bool tie = active && split_failed && clo > target;
     int idcut = 0xFFFF;
@@ -134,22 +136,13 @@ __device__ __noinline__ Refreshed refresh_fast(List L, int k, int target, int cn
         for (int it = 0; it < 16; ++it) {
             int mid = (ilo + ihi) >> 1;
             int ce = 0;
-            for (int i = 0; i < CAPL; ++i) {
-                if (i < cnt) {
-                    float v = L.cv[32 * i];
-                    int id = L.ci[32 * i];
-                    ce += (v == lo && id <= mid) ? 1 : 0;
-                }
-            }
+#pragma unroll
+            for (int i = 0; i < CAPL; ++i) ce += (r[i] == lo && i < cnt && (int)ids[i] <= mid) ? 1 : 0;
             ce += __shfl_xor(ce, 32);
             if (ce >= need) ihi = mid; else ilo = mid;
         }
         idcut = ihi;
     }
-    // compaction: all ids are fetched up front (one wait), then survivors are written back in order
-    uint16_t ids[CAPL];
-#pragma unroll
-    for (int i = 0; i < CAPL; ++i) ids[i] = L.ci[32 * i];
     int jw = 0;
 #pragma unroll
     for (int i = 0; i < CAPL; ++i) {
@@ -177,18 +170,19 @@ __device__ __forceinline__ uint2 split_bias(float b) {
     return make_uint2((u0 >> 16) | u1, u2 >> 16);
 }
 
-template <int DH>
+template <int DH, int ABL>
 __global__ __launch_bounds__(kThreads) void sae_encode_topk_fast_kernel(EncParams p) {
     constexpr int NS = DH / 16;
     constexpr int RB = DH * ES;
     constexpr int ROWB = RB + 16;          // W row + 16-byte pad that carries the bias terms
     constexpr int VR = RB / 16;
-    constexpr int NV = (kFT * VR + kThreads - 1) / kThreads;
+    constexpr int NV = kFT * VR / kThreads;
+    static_assert(kFT * VR % kThreads == 0, "a stage must divide evenly over the workgroup");
 
     extern __shared__ __align__(16) char smem[];
     char* wst = smem;                                              // [2][kFT][ROWB]
-    int* vote = (int*)(smem + 2 * kFT * ROWB);                     // [4] refresh votes (3 used, rotating)
-    float* cval_all = (float*)(vote + 4);                          // [kWaves][2 CAPL][32]
+    lds_i32* vote = (lds_i32*)(smem + 2 * kFT * ROWB);             // [4] refresh votes, slot = step & 3
+    float* cval_all = (float*)(smem + 2 * kFT * ROWB + 16);        // [kWaves][2 CAPL][32]
     uint16_t* cid_all = (uint16_t*)(cval_all + kWaves * 2 * CAPL * 32);
 
     const int tid = threadIdx.x, lane = tid & 63;
@@ -199,13 +193,12 @@ __global__ __launch_bounds__(kThreads) void sae_encode_topk_fast_kernel(EncParam
     const int tok = tt * kTokWG + wv * 32 + n;
     const bool tok_ok = tok < p.T;
 
-    const char* xh = p.x + (size_t)head * p.T * RB;
     const char* wh = p.w + (size_t)head * p.n_feat * RB;
     const float* bh = p.b + (size_t)head * p.n_feat;
 
     bf16x8 bfr[NS];
     {
-        const char* row = xh + (size_t)(tok_ok ? tok : 0) * RB;
+        const char* row = p.x + ((size_t)head * p.T + (tok_ok ? tok : 0)) * RB;
 #pragma unroll
         for (int s = 0; s < NS; ++s) {
             uint4 u = tok_ok ? *(const uint4*)(row + (16 * s + 8 * half) * ES) : make_uint4(0, 0, 0, 0);
@@ -222,163 +215,184 @@ __global__ __launch_bounds__(kThreads) void sae_encode_topk_fast_kernel(EncParam
     List L;
     L.cv = pv0;
     L.ci = pi0;
+    lds_f32* pv = pv0;
+    lds_u16* pi = pi0;
     lds_f32* const pv_full = pv0 + (CAPL - kGuard) * 32;           // above this a group of 4 may not fit
     lds_f32* const pv_soft = pv0 + p.soft * 32;                    // above this the lane asks for a voted refresh
+    float tau = (ABL & kNoHits) ? INFINITY : -INFINITY;
     const int k = p.k;
     const int loose = min(k + (k >> 3) + 2, CAPL - kGuard);
     const int nst = (p.n_feat + kFT - 1) / kFT;
-    // the second wavefront of each SIMD runs half a stage behind (which wavefronts share a SIMD: p.skew)
-    const bool late = p.skew ? (wv & 1) : (wv >= kWaves / 2);
+    const int nfull = p.n_feat / kFT;                              // stages before this one have all kFT rows
 
-    // global -> register -> LDS copy of one stage: this thread's 16-byte pieces and (tid < kFT) one bias
+    // global -> register -> LDS copy of one stage: NV 16-byte pieces per thread, wavefront 0 also one bias per lane
     int goff[NV], loff[NV], grow[NV];
 #pragma unroll
     for (int i = 0; i < NV; ++i) {
         int v = tid + i * kThreads;
-        grow[i] = v < kFT * VR ? v / VR : 0x7FFFFFFF;
-        int col = v % VR;
-        goff[i] = grow[i] * RB + col * 16;
-        loff[i] = grow[i] * ROWB + col * 16;
+        grow[i] = v / VR;
+        goff[i] = grow[i] * RB + (v % VR) * 16;
+        loff[i] = grow[i] * ROWB + (v % VR) * 16;
     }
-    // Two register sets: stage s travels in set s & 1, is requested two steps before it is used and
+    // The stage loop is written with macros over plain local variables (no closures), so that every piece
+    // of state stays in registers.
+    //
+    // Two register sets (A, B): stage s travels in set s & 1, is requested two steps before it is used and
     // written to LDS one step before, so a load has two whole steps to arrive.
-    uint4 wset[2][NV];
-    uint2 bset[2] = {make_uint2(0, 0), make_uint2(0, 0)};
-    auto gload = [&](int j, uint4 (&wreg)[NV], uint2& breg) {
-        const int left = p.n_feat - j * kFT;                      // rows of this stage that exist
-        const char* base = wh + (size_t)j * kFT * RB;
-#pragma unroll
-        for (int i = 0; i < NV; ++i)
-            wreg[i] = grow[i] < left ? *(const uint4*)(base + goff[i]) : make_uint4(0, 0, 0, 0);
-        if (tid < kFT) breg = tid < left ? split_bias(bh[j * kFT + tid]) : make_uint2(0xFF80u, 0);   // missing row: -inf
-    };
-    auto sstore = [&](int buf, const uint4 (&wreg)[NV], const uint2& breg) {
-        char* base = wst + buf * kFT * ROWB;
-#pragma unroll
-        for (int i = 0; i < NV; ++i)
-            if (grow[i] != 0x7FFFFFFF) *(uint4*)(base + loff[i]) = wreg[i];
-        if (tid < kFT) *(uint4*)(base + tid * ROWB + RB) = make_uint4(breg.x, breg.y, 0, 0);
-    };
+    uint4 wA0, wA1, wB0, wB1;
+    uint2 bA = make_uint2(0, 0), bB = make_uint2(0, 0);
+    wA1 = wB1 = make_uint4(0, 0, 0, 0);
+
+#define S3_GLOAD(J, W0, W1, BR)                                                                              \
+    do {                                                                                                     \
+        const int j_ = (J);                                                                                  \
+        const char* base_ = wh + (size_t)j_ * kFT * RB;                                                      \
+        if (j_ < nfull) { /* hot path: no predication */                                                     \
+            W0 = *(const uint4*)(base_ + goff[0]);                                                           \
+            if (NV > 1) W1 = *(const uint4*)(base_ + goff[NV - 1]);                                          \
+            if (wv == 0) BR = split_bias(bh[j_ * kFT + lane]);                                               \
+        } else { /* last, partial stage: missing rows are zero with bias -inf */                             \
+            const int left_ = p.n_feat - j_ * kFT;                                                           \
+            W0 = grow[0] < left_ ? *(const uint4*)(base_ + goff[0]) : make_uint4(0, 0, 0, 0);                \
+            if (NV > 1) W1 = grow[NV - 1] < left_ ? *(const uint4*)(base_ + goff[NV - 1]) : make_uint4(0, 0, 0, 0); \
+            if (wv == 0) BR = lane < left_ ? split_bias(bh[j_ * kFT + lane]) : make_uint2(0xFF80u, 0);       \
+        }                                                                                                    \
+    } while (0)
+
+#define S3_SSTORE(BUF, W0, W1, BR)                                                                           \
+    do {                                                                                                     \
+        char* base_ = wst + (BUF) * kFT * ROWB;                                                              \
+        *(uint4*)(base_ + loff[0]) = W0;                                                                     \
+        if (NV > 1) *(uint4*)(base_ + loff[NV - 1]) = W1;                                                    \
+        if (wv == 0) *(uint4*)(base_ + lane * ROWB + RB) = make_uint4(BR.x, BR.y, 0, 0);                     \
+    } while (0)
 
     f32x16 acc0, acc1;
-    auto mma = [&](int cur) {
-        const char* a0 = wst + (cur * kFT + n) * ROWB;
-        const char* a1 = a0 + 32 * ROWB;
-        const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-        uint4 f0[NS + 1], f1[NS + 1];
-        f0[NS] = *(const uint4*)(a0 + RB);                        // bias terms (same address for both lanes of a token)
-        f1[NS] = *(const uint4*)(a1 + RB);
-#pragma unroll
-        for (int s = 0; s < NS; ++s) {
-            f0[s] = *(const uint4*)(a0 + 16 * half + 32 * s);
-            f1[s] = *(const uint4*)(a1 + 16 * half + 32 * s);
-        }
-        acc0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, f0[NS]), bones, zero, 0, 0, 0);
-        acc1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, f1[NS]), bones, zero, 0, 0, 0);
-#pragma unroll
-        for (int s = 0; s < NS; ++s) {
-            acc0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, f0[s]), bfr[s], acc0, 0, 0, 0);
-            acc1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, f1[s]), bfr[s], acc1, 0, 0, 0);
-        }
-    };
+    const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 
-    int cnt = 0;
-    for (int attempt = 0; attempt < 2; ++attempt) {
-        lds_f32* pv = pv0;
-        lds_u16* pi = pi0;
-        float tau = p.ablate ? INFINITY : -INFINITY;
-        bool guess = attempt == 0 && p.opt_c > 0.f && nst >= 4 && !p.ablate;    // optimistic start (first attempt only)
-        if (tid < 4) vote[tid] = 0;
-        gload(0, wset[0], bset[0]);
-        sstore(0, wset[0], bset[0]);
-        if (nst > 1) gload(1, wset[1], bset[1]);
-        __syncthreads();
+#define S3_MMA(CUR)                                                                                          \
+    do {                                                                                                     \
+        if (ABL & kNoMfma) break;                                                                            \
+        const char* a0_ = wst + ((CUR) * kFT + n) * ROWB;                                                    \
+        const char* a1_ = a0_ + 32 * ROWB;                                                                   \
+        {   /* bias terms: same address for both lanes of a token */                                         \
+            uint4 g0_ = *(const uint4*)(a0_ + RB), g1_ = *(const uint4*)(a1_ + RB);                          \
+            acc0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, g0_), bones, zero, 0, 0, 0); \
+            acc1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, g1_), bones, zero, 0, 0, 0); \
+        }                                                                                                    \
+        _Pragma("unroll") for (int s = 0; s < NS; s += 2) {   /* two K steps at a time keeps few fragments live */ \
+            uint4 f00_ = *(const uint4*)(a0_ + 16 * half + 32 * s);                                          \
+            uint4 f10_ = *(const uint4*)(a1_ + 16 * half + 32 * s);                                          \
+            uint4 f01_ = *(const uint4*)(a0_ + 16 * half + 32 * s + 32);                                     \
+            uint4 f11_ = *(const uint4*)(a1_ + 16 * half + 32 * s + 32);                                     \
+            acc0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, f00_), bfr[s], acc0, 0, 0, 0); \
+            acc1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, f10_), bfr[s], acc1, 0, 0, 0); \
+            acc0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, f01_), bfr[s + 1], acc0, 0, 0, 0); \
+            acc1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, f11_), bfr[s + 1], acc1, 0, 0, 0); \
+        }                                                                                                    \
+    } while (0)
 
-        // one step of the stage loop; PAR = j & 1 is a compile-time constant (the loop is unrolled by two)
-        auto step = [&](const int j, auto par) {
-            constexpr int cur = decltype(par)::value;
-            if (j + 2 < nst && !(p.ablate & 2)) gload(j + 2, wset[cur], bset[cur]);
-            // vote of the previous step (written before the last barrier); cleared two steps later
-            const int voted = j > 0 ? __builtin_amdgcn_readfirstlane(vote[(j - 1) % 3]) : 0;
-            if (tid == 0 && j > 1) vote[(j - 2) % 3] = 0;
-            if (!late && j < nst && !(p.ablate & 8)) mma(cur);
-            if (p.ablate & 4) {
-                asm volatile("" ::"v"(acc0[0]), "v"(acc1[0]), "v"(acc0[15]), "v"(acc1[15]));
-            } else if (late ? (j > 0) : (j < nst)) {
-                if (guess) {    // the wavefront's first 64 pre-activations per token: tau = mean + c * std
-                    float s1 = 0.f, s2 = 0.f;
-#pragma unroll
-                    for (int r = 0; r < 16; ++r) {
-                        s1 += acc0[r] + acc1[r];
-                        s2 = fmaf(acc0[r], acc0[r], fmaf(acc1[r], acc1[r], s2));
-                    }
-                    s1 += __shfl_xor(s1, 32);
-                    s2 += __shfl_xor(s2, 32);
-                    const float mean = s1 * (1.f / 64.f);
-                    const float var = fmaxf(s2 * (1.f / 64.f) - mean * mean, 0.f);
-                    const float t0 = mean + p.opt_c * sqrtf(var);
-                    tau = (t0 == t0 && fabsf(t0) < INFINITY) ? t0 : -INFINITY;
-                    guess = false;
-                }
-                if (voted && !p.ablate) {     // every wavefront of the workgroup refreshes in this step
-                    if (p.dbg && lane == 0) atomicAdd(&p.dbg[1], 1ull);
-                    Refreshed r = refresh_fast(L, k, loose, (int)(pv - pv0) >> 5, tau, p.dbg);
-                    tau = r.tau;
-                    pv = pv0 + r.cnt * 32;
-                    pi = pi0 + r.cnt * 32;
-                }
-                // compare/append epilogue of one stage: 8 groups of 4 accumulators.  One uniform branch per
-                // group skips it when no lane of the wavefront has a survivor.  Every lane has >= kGuard
-                // free slots at the start of a group (checked after each group that appended).
-                const unsigned fb = (unsigned)((late ? j - 1 : j) * kFT + half * 4);
-#pragma unroll
-                for (int g = 0; g < 8; ++g) {
-                    const float a0 = g < 4 ? acc0[(g & 3) * 4 + 0] : acc1[(g & 3) * 4 + 0];
-                    const float a1 = g < 4 ? acc0[(g & 3) * 4 + 1] : acc1[(g & 3) * 4 + 1];
-                    const float a2 = g < 4 ? acc0[(g & 3) * 4 + 2] : acc1[(g & 3) * 4 + 2];
-                    const float a3 = g < 4 ? acc0[(g & 3) * 4 + 3] : acc1[(g & 3) * 4 + 3];
-                    const bool h0 = a0 > tau, h1 = a1 > tau, h2 = a2 > tau, h3 = a3 > tau;
-                    if (__any(h0 || h1 || h2 || h3)) {
-                        constexpr unsigned kIdBase = 0;
-                        const unsigned idb = fb + (g >> 2) * 32 + (g & 3) * 8 + kIdBase;
-                        if (h0) { *pv = a0; *pi = (uint16_t)(idb + 0); pv += 32; pi += 32; }
-                        if (h1) { *pv = a1; *pi = (uint16_t)(idb + 1); pv += 32; pi += 32; }
-                        if (h2) { *pv = a2; *pi = (uint16_t)(idb + 2); pv += 32; pi += 32; }
-                        if (h3) { *pv = a3; *pi = (uint16_t)(idb + 3); pv += 32; pi += 32; }
-                        if (__any(pv > pv_full)) {     // emergency: a list may not take another group
-                            if (p.dbg && lane == 0) atomicAdd(&p.dbg[0], 1ull);
-                            Refreshed r = refresh_fast(L, k, loose, (int)(pv - pv0) >> 5, tau, p.dbg);
-                            tau = r.tau;
-                            pv = pv0 + r.cnt * 32;
-                            pi = pi0 + r.cnt * 32;
-                        }
-                    }
-                }
-                if (p.soft > 0 && __any(pv > pv_soft) && lane == 0) vote[j % 3] = 1;
-            }
-            if (late && j < nst && !(p.ablate & 8)) mma(cur);
-            if (j + 1 < nst && !(p.ablate & 2)) sstore(cur ^ 1, wset[cur ^ 1], bset[cur ^ 1]);
-            if (j < nst) __syncthreads();
-        };
-        for (int j = 0; j <= nst; j += 2) {
-            step(j, std::integral_constant<int, 0>{});
-            if (j + 1 <= nst) step(j + 1, std::integral_constant<int, 1>{});
-        }
+#define S3_REFRESH(TARGET)                                                                                   \
+    do {                                                                                                     \
+        Refreshed r_ = refresh_fast(L, k, (TARGET), (int)(pv - pv0) >> 5, tau);                              \
+        tau = r_.tau;                                                                                        \
+        pv = pv0 + r_.cnt * 32;                                                                              \
+        pi = pi0 + r_.cnt * 32;                                                                              \
+    } while (0)
 
-        // exactly k per token; a token with fewer than k candidates above its optimistic tau failed the guess
-        Refreshed r = refresh_fast(L, k, k, (int)(pv - pv0) >> 5, tau, p.dbg);
-        cnt = r.cnt;
-        const int total = cnt + __shfl_xor(cnt, 32);
-        const bool failed = tok_ok && total < k && !p.ablate;
-        if (p.dbg) {
-            if (failed && half == 0) atomicAdd(&p.dbg[2], 1ull);
-            if (lane == 0) atomicAdd(&p.dbg[4], 1ull);
-        }
-        if (!__syncthreads_or(failed ? 1 : 0)) break;
+#define S3_APPEND(H, A, IDV)                                                                                 \
+    if (H) {                                                                                                 \
+        *pv = (A);                                                                                           \
+        *pi = (uint16_t)(IDV);                                                                               \
+        pv += 32;                                                                                            \
+        pi += 32;                                                                                            \
     }
 
-    // bitonic sort of each token's k candidates: lanes 0-31 sort token 2 it, lanes 32-63 token 2 it + 1;
-    // order (z descending, id ascending); lane e ends up with rank e.
+    // Compare/append of one group of 4 accumulators (features FB + 0..3): one uniform branch skips it when
+    // no lane of the wavefront has a survivor.  Every lane has >= kGuard free slots at the start of a group
+    // (checked after each group that appended).  The id base is made opaque inside the branch so that ids
+    // are formed only when something is appended.
+#define S3_GROUP(A0, A1, A2, A3, FB)                                                                         \
+    do {                                                                                                     \
+        const float a0_ = (A0), a1_ = (A1), a2_ = (A2), a3_ = (A3);                                          \
+        const bool h0_ = a0_ > tau, h1_ = a1_ > tau, h2_ = a2_ > tau, h3_ = a3_ > tau;                       \
+        if (__any(h0_ || h1_ || h2_ || h3_)) {                                                               \
+            unsigned idb_ = (FB);                                                                            \
+            asm volatile("" : "+v"(idb_));                                                                   \
+            S3_APPEND(h0_, a0_, idb_ + 0)                                                                    \
+            S3_APPEND(h1_, a1_, idb_ + 1)                                                                    \
+            S3_APPEND(h2_, a2_, idb_ + 2)                                                                    \
+            S3_APPEND(h3_, a3_, idb_ + 3)                                                                    \
+            if (__any(pv > pv_full)) S3_REFRESH(loose); /* emergency: a list may not take another group */   \
+        }                                                                                                    \
+    } while (0)
+
+    // Epilogue of the stage whose first feature is F0; STEPNO = current step; VOTED: the workgroup agreed in
+    // the previous step to refresh now.
+#define S3_EPILOGUE(F0, STEPNO, VOTED)                                                                       \
+    do {                                                                                                     \
+        if (ABL & kNoEpilogue) {                                                                             \
+            asm volatile("" ::"v"(acc0[0]), "v"(acc1[0]), "v"(acc0[15]), "v"(acc1[15]));                     \
+            break;                                                                                           \
+        }                                                                                                    \
+        if (VOTED) S3_REFRESH(loose);                                                                        \
+        const unsigned fb_ = (unsigned)((F0) + half * 4);                                                    \
+        S3_GROUP(acc0[0], acc0[1], acc0[2], acc0[3], fb_ + 0);                                               \
+        S3_GROUP(acc0[4], acc0[5], acc0[6], acc0[7], fb_ + 8);                                               \
+        S3_GROUP(acc0[8], acc0[9], acc0[10], acc0[11], fb_ + 16);                                            \
+        S3_GROUP(acc0[12], acc0[13], acc0[14], acc0[15], fb_ + 24);                                          \
+        S3_GROUP(acc1[0], acc1[1], acc1[2], acc1[3], fb_ + 32);                                              \
+        S3_GROUP(acc1[4], acc1[5], acc1[6], acc1[7], fb_ + 40);                                              \
+        S3_GROUP(acc1[8], acc1[9], acc1[10], acc1[11], fb_ + 48);                                            \
+        S3_GROUP(acc1[12], acc1[13], acc1[14], acc1[15], fb_ + 56);                                          \
+        if (__any(pv > pv_soft) && lane == 0) vote[(STEPNO) & 3] = 1;                                        \
+    } while (0)
+
+    // One step of the stage loop.  CUR = step & 1 is a literal (the loop is unrolled by two); LATE selects
+    // the order of MFMA and epilogue.  (WL*, BL) is the register set to load stage j + 2 into, (WS*, BS) the
+    // set whose stage j + 1 is written to LDS.
+#define S3_STEP(J, CUR, LATE, WL0, WL1, BL, WS0, WS1, BS)                                                    \
+    do {                                                                                                     \
+        const int js_ = (J);                                                                                 \
+        if (!(ABL & kNoLoads) && js_ + 2 < nst) S3_GLOAD(js_ + 2, WL0, WL1, BL);                             \
+        const int voted_ = (p.soft > 0 && js_ > 0) ? __builtin_amdgcn_readfirstlane(vote[(js_ - 1) & 3]) : 0; \
+        if (tid == 0 && js_ > 1) vote[(js_ - 2) & 3] = 0;                                                    \
+        if (!(LATE)) {                                                                                       \
+            S3_MMA(CUR);                                                                                     \
+            S3_EPILOGUE(js_* kFT, js_, voted_);                                                              \
+        } else {                                                                                             \
+            if (js_ > 0) S3_EPILOGUE((js_ - 1) * kFT, js_, voted_);                                          \
+            S3_MMA(CUR);                                                                                     \
+        }                                                                                                    \
+        if (!(ABL & kNoLoads) && js_ + 1 < nst) S3_SSTORE((CUR) ^ 1, WS0, WS1, BS);                          \
+        __syncthreads();                                                                                     \
+    } while (0)
+
+    if (tid < 4) vote[tid] = 0;
+    S3_GLOAD(0, wA0, wA1, bA);
+    S3_SSTORE(0, wA0, wA1, bA);
+    if (nst > 1) S3_GLOAD(1, wB0, wB1, bB);
+    __syncthreads();
+
+    // Wavefronts 0-3 (early) handle stage j in step j; wavefronts 4-7 (late) run the epilogue of stage j - 1
+    // first, so that the two wavefronts of a SIMD use the matrix pipe and the vector ALU at different times.
+    if (wv < kWaves / 2) {
+        for (int j = 0; j < nst; j += 2) {
+            S3_STEP(j, 0, false, wA0, wA1, bA, wB0, wB1, bB);
+            if (j + 1 < nst) S3_STEP(j + 1, 1, false, wB0, wB1, bB, wA0, wA1, bA);
+        }
+    } else {
+        for (int j = 0; j < nst; j += 2) {
+            S3_STEP(j, 0, true, wA0, wA1, bA, wB0, wB1, bB);
+            if (j + 1 < nst) S3_STEP(j + 1, 1, true, wB0, wB1, bB, wA0, wA1, bA);
+        }
+        S3_EPILOGUE((nst - 1) * kFT, nst, 0);
+    }
+
+    // exactly k per token, then a bitonic sort of each token's k candidates: lanes 0-31 sort token 2 it,
+    // lanes 32-63 token 2 it + 1; order (z descending, id ascending); lane e ends up with rank e.
+    S3_REFRESH(k);
+    const int cnt = (int)(pv - pv0) >> 5;
     int32_t* ids_h = p.ids + (size_t)head * p.T * k;
     float* vals_h = p.vals + (size_t)head * p.T * k;
     const int tok0 = tt * kTokWG + wv * 32;
@@ -413,11 +427,11 @@ __global__ __launch_bounds__(kThreads) void sae_encode_topk_fast_kernel(EncParam
     }
 }
 
-template <int DH>
+template <int DH, int ABL>
 int launch_fast(EncParams p, hipStream_t st) {
     constexpr int ROWB = DH * ES + 16;
-    const size_t lds = 2 * kFT * ROWB + 4 * sizeof(int) + (size_t)kWaves * 2 * CAPL * 32 * (sizeof(float) + sizeof(uint16_t));
-    auto kern = sae_encode_topk_fast_kernel<DH>;
+    const size_t lds = 2 * kFT * ROWB + 16 + (size_t)kWaves * 2 * CAPL * 32 * (sizeof(float) + sizeof(uint16_t));
+    auto kern = sae_encode_topk_fast_kernel<DH, ABL>;
     static bool attr_set = false;
     if (!attr_set) {
         S3_HIP(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
@@ -432,35 +446,19 @@ int launch_fast(EncParams p, hipStream_t st) {
 
 }  // namespace
 
-// Tuning aid (not part of the public header): with S3_ENC_DBG=1 in the environment the fast kernel counts
-// [0] emergency refreshes, [1] voted refreshes, [2] tokens whose optimistic start failed, [4] wavefront passes.
-static unsigned long long* g_dbg = nullptr;
-
-extern "C" int s3_debug_counters(unsigned long long* out8) {
-    if (!g_dbg || !out8) return S3_EINVAL;
-    if (hipDeviceSynchronize() != hipSuccess) return S3_EHIP;
-    if (hipMemcpy(out8, g_dbg, 8 * sizeof(unsigned long long), hipMemcpyDeviceToHost) != hipSuccess) return S3_EHIP;
-    if (hipMemset(g_dbg, 0, 8 * sizeof(unsigned long long)) != hipSuccess) return S3_EHIP;
-    return S3_OK;
-}
-
 int s3_encode_fast_launch(EncParams p, int d_head, hipStream_t st) {
-    p.dbg = nullptr;
-    if (env_int("S3_ENC_DBG", 0)) {
-        if (!g_dbg) {
-            S3_HIP(hipMalloc(&g_dbg, 8 * sizeof(unsigned long long)));
-            S3_HIP(hipMemset(g_dbg, 0, 8 * sizeof(unsigned long long)));
-        }
-        p.dbg = g_dbg;
-    }
     static_assert(CAPL >= 32 + kGuard, "a lane must be able to hold k survivors and one more group");
-    p.opt_c = 0.01f * (float)env_int("S3_ENC_OPT_C", 230);         // optimistic start: tau0 = mean + c * std
-    p.skew = env_int("S3_ENC_SKEW", 1);
     p.soft = env_int("S3_ENC_SOFT", 33);                           // list length that asks for a voted refresh (0 = off)
     if (p.soft < 0 || p.soft > CAPL - kGuard) return s3_fail(S3_EINVAL, "s3_sae_encode_topk: bad S3_ENC_SOFT");
-    switch (d_head) {
-        case 64: return launch_fast<64>(p, st);
-        case 128: return launch_fast<128>(p, st);
+    if (d_head == 64) return launch_fast<64, 0>(p, st);
+    if (d_head != 128) return s3_fail(S3_EINVAL, "s3_sae_encode_topk: unsupported d_head %d", d_head);
+    switch (p.ablate) {       // tuning builds: parts of the kernel compiled out (results are then meaningless)
+        case 0: return launch_fast<128, 0>(p, st);
+        case 1: return launch_fast<128, kNoHits>(p, st);
+        case 7: return launch_fast<128, kNoHits | kNoLoads | kNoEpilogue>(p, st);
+        case 11: return launch_fast<128, kNoHits | kNoLoads | kNoMfma>(p, st);
+        case 13: return launch_fast<128, kNoHits | kNoEpilogue | kNoMfma>(p, st);
+        case 15: return launch_fast<128, 15>(p, st);
     }
-    return s3_fail(S3_EINVAL, "s3_sae_encode_topk: unsupported d_head %d", d_head);
+    return s3_fail(S3_EINVAL, "s3_sae_encode_topk: S3_ENC_ABLATE %d is not built", p.ablate);
 }
