@@ -372,7 +372,7 @@ extern "C" int s3_sae_encode_topk(const void* x, int dtype, int T, int d_head, c
     p.T = T; p.n_feat = n_feat; p.k = k; p.n_heads = n_heads;
     p.ablate = env_int("S3_ENC_ABLATE", 0);
     hipStream_t st = (hipStream_t)stream;
-    if (dtype == S3_BF16 && k <= 32 && d_head <= 128 && env_int("S3_ENC_GENERIC", 0) == 0) return s3_encode_fast_launch(p, d_head, st);
+    if (s3_encode_fast_ok(dtype, d_head, n_feat, k) && env_int("S3_ENC_GENERIC", 0) == 0) return s3_encode_fast_launch(p, st);
     p.tiles_per_head = (T + kTokWG - 1) / kTokWG;
     // list capacity per token: k survivors + headroom for one tile + room for new candidates between refreshes
     int capt = k + kHeadroom + (k <= 32 ? 16 : 32);

@@ -1,14 +1,17 @@
-// Fast path of the fused SAE encoder + Top-k (Sec. 3.3) for bf16 inputs and k <= 32.
+// Fast path of the fused SAE encoder + Top-k (Sec. 3.3): bf16, d_head = 128, k <= 32,
+// n_feat a multiple of 32.
 //
 // Same method as the generic kernel (features on the MFMA M axis, per-token threshold tau,
 // candidate lists in LDS, exact selection), laid out for two wavefronts per SIMD:
 //
-//   - workgroup = 8 wavefronts = 256 tokens; a stage of 64 features (two 32x32 MFMA tiles per
-//     wavefront) is staged once per workgroup through LDS, double-buffered, one barrier per stage;
-//     global loads run two stages ahead in two alternating register sets;
-//   - b_enc rides in the GEMM: each staged W row carries the bias split exactly into three bf16
-//     terms in its 16-byte pad, multiplied by a constant [1, 1, 1, 0...] operand in a ninth K step,
-//     so accumulators start from the literal 0 and no bias is read or added by the vector ALU;
+//   - workgroup = 8 wavefronts = 256 tokens.  W_enc streams through a ring of four 32-feature
+//     stages in LDS.  Each wavefront copies 4 rows of a stage per step straight from global memory
+//     into LDS (no registers in between), three stages ahead of the MFMAs, so a copy has three
+//     whole steps to arrive; one barrier per stage;
+//   - rows are 256 bytes, unpadded; the sixteen 16-byte pieces of row r are stored at piece index
+//     (c xor (r & 15)), which makes the 16-byte fragment reads of 16 consecutive rows conflict-free;
+//   - b_enc is copied the same way (fp32) and read as the accumulator's initial value, so the
+//     bias costs no vector-ALU instruction;
 //   - wavefronts 0-3 run [MFMA(j), epilogue(j)], wavefronts 4-7 run [epilogue(j-1), MFMA(j)]: the
 //     two wavefronts that share a SIMD are half a stage apart, so one feeds the matrix pipe while
 //     the other runs the compare/append epilogue on the vector ALU;
@@ -17,33 +20,78 @@
 //     appended;
 //   - threshold refreshes are voted per workgroup at the stage barrier, so that all wavefronts
 //     refresh in the same stage instead of stalling each other one after the other; the refresh
-//     loads the lane's candidates into registers once and narrows tau there;
+//     loads the lane's candidates into registers once and narrows tau there.  The kernel has ONE
+//     refresh site (voted, emergency and final refresh all pass through it), inlined;
 //   - the final k candidates of a token are sorted with a 32-lane bitonic network (two tokens per
 //     wavefront step) and written coalesced.
+//
+// LDS accesses inside the stage loop (fragment reads, list appends, votes) are written as inline
+// assembly: the compiler orders every LDS access it knows of behind ALL outstanding global->LDS
+// copies (it cannot tell which bytes a copy writes), which would drain the copy pipeline in every step.
+// The waits that the ring really needs are the explicit s_waitcnt before each barrier.
 #include "s3_common.h"
 
+#include <float.h>
 #include <math.h>
-
-#include <type_traits>
 
 namespace {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(4))) unsigned u32x4;
 
 constexpr int kThreads = 512;
 constexpr int kWaves = 8;
 constexpr int kTokWG = 256;
-constexpr int kFT = 64;          // features per stage
+constexpr int kFT = 32;          // features per stage (one 32x32 MFMA tile per wavefront)
+constexpr int kRing = 4;         // stages in the LDS ring
+constexpr int kAhead = kRing - 1;
+constexpr int DH = 128;
+constexpr int NS = DH / 16;      // MFMA K steps per stage
+constexpr int RB = DH * 2;       // bytes of one W row
+constexpr int kStageB = kFT * RB;
+constexpr int kBiasB = 256;      // 32 fp32 biases, copied twice (a wavefront-wide copy is 64 lanes wide)
 constexpr int CAPL = 40;         // list slots per lane (a token has two lanes)
 constexpr int kGuard = 4;        // appends possible between two fullness checks
-constexpr int ES = 2;
+constexpr int kOffBias = kRing * kStageB;
+constexpr int kOffVote = kOffBias + kRing * kBiasB;
+constexpr int kOffVal = kOffVote + 16;
+constexpr int kOffId = kOffVal + kWaves * 2 * CAPL * 32 * 4;
+constexpr int kLdsBytes = kOffId + kWaves * 2 * CAPL * 32 * 2;
 typedef __attribute__((address_space(3))) float lds_f32;
 typedef __attribute__((address_space(3))) uint16_t lds_u16;
-typedef __attribute__((address_space(3))) int lds_i32;
+typedef __attribute__((address_space(3))) void lds_void;
+typedef __attribute__((address_space(3))) char lds_char;
+typedef __attribute__((address_space(1))) const void glb_cvoid;
 
 // compile-time ablation masks of the tuning builds (0 in the product kernel)
-constexpr int kNoHits = 1, kNoLoads = 2, kNoEpilogue = 4, kNoMfma = 8;
+constexpr int kNoHits = 1, kProfile = 16;
+
+// kProfile build: cycles per phase, summed over the steps of wavefronts 0 and 4 of workgroup 0
+__device__ unsigned long long s3_prof[32];
+
+__device__ __forceinline__ void lds_store_f32(unsigned addr, float v) {
+    asm volatile("ds_write_b32 %0, %1" ::"v"(addr), "v"(v) : "memory");
+}
+__device__ __forceinline__ void lds_store_u16(unsigned addr, unsigned v) {
+    asm volatile("ds_write_b16 %0, %1" ::"v"(addr), "v"(v) : "memory");
+}
+__device__ __forceinline__ void lds_store_u32(unsigned addr, unsigned v) {
+    asm volatile("ds_write_b32 %0, %1" ::"v"(addr), "v"(v) : "memory");
+}
+__device__ __forceinline__ unsigned lds_load_u32(unsigned addr) {
+    unsigned v;
+    asm volatile("ds_read_b32 %0, %1\n\ts_waitcnt lgkmcnt(0)" : "=&v"(v) : "v"(addr) : "memory");
+    return v;
+}
+
+// Waits until at most N of this wavefront's global->LDS copies are in flight and all its LDS accesses are
+// done, then joins the workgroup barrier.
+template <int N>
+__device__ __forceinline__ void stage_barrier() {
+    asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(N) : "memory");
+}
 
 __device__ __forceinline__ unsigned ordered_key(float v) {
     unsigned u = __float_as_uint(v);
@@ -53,70 +101,118 @@ __device__ __forceinline__ float key_value(unsigned k) {
     return __uint_as_float(k ^ ((k >> 31) ? 0x80000000u : 0xFFFFFFFFu));
 }
 
-// One lane's candidate list: slot i lives at cv[32 i] / ci[32 i] (LDS address space, so that the
-// compiler emits ds_read/ds_write rather than flat accesses).
-struct List {
-    lds_f32* cv;
-    lds_u16* ci;
-};
+// x of this lane combined with x of the token's other lane (lane ^ 32): one cross-half swap, no LDS
+__device__ __forceinline__ int pair_sum(int x) {
+    auto r = __builtin_amdgcn_permlane32_swap((unsigned)x, (unsigned)x, false, false);
+    return (int)(r[0] + r[1]);
+}
+__device__ __forceinline__ float pair_max(float x) {
+    auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+__device__ __forceinline__ float pair_min(float x) {
+    auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    return fminf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
 
+// Number of this token's candidates >= m (both lanes).  Ten compares into ten scalar masks, then ten
+// add-with-carry on two alternating counters: written out so that no instruction waits for the one before it.
 __device__ __forceinline__ int count_ge_regs(const float (&r)[CAPL], float m) {
-    int c = 0;
+    static_assert(CAPL % 10 == 0, "count_ge_regs works in blocks of ten");
+    int c0 = 0, c1 = 0;
 #pragma unroll
-    for (int i = 0; i < CAPL; ++i) c += (r[i] >= m) ? 1 : 0;
-    return c + __shfl_xor(c, 32);
+    for (int b = 0; b < CAPL; b += 10) {
+        unsigned long long m0, m1, m2, m3, m4, m5, m6, m7, m8, m9;
+        asm("v_cmp_ge_f32_e64 %2, %12, %22\n\t"
+            "v_cmp_ge_f32_e64 %3, %13, %22\n\t"
+            "v_cmp_ge_f32_e64 %4, %14, %22\n\t"
+            "v_cmp_ge_f32_e64 %5, %15, %22\n\t"
+            "v_cmp_ge_f32_e64 %6, %16, %22\n\t"
+            "v_cmp_ge_f32_e64 %7, %17, %22\n\t"
+            "v_cmp_ge_f32_e64 %8, %18, %22\n\t"
+            "v_cmp_ge_f32_e64 %9, %19, %22\n\t"
+            "v_cmp_ge_f32_e64 %10, %20, %22\n\t"
+            "v_cmp_ge_f32_e64 %11, %21, %22\n\t"
+            "v_addc_co_u32_e64 %0, vcc, 0, %0, %2\n\t"
+            "v_addc_co_u32_e64 %1, vcc, 0, %1, %3\n\t"
+            "v_addc_co_u32_e64 %0, vcc, 0, %0, %4\n\t"
+            "v_addc_co_u32_e64 %1, vcc, 0, %1, %5\n\t"
+            "v_addc_co_u32_e64 %0, vcc, 0, %0, %6\n\t"
+            "v_addc_co_u32_e64 %1, vcc, 0, %1, %7\n\t"
+            "v_addc_co_u32_e64 %0, vcc, 0, %0, %8\n\t"
+            "v_addc_co_u32_e64 %1, vcc, 0, %1, %9\n\t"
+            "v_addc_co_u32_e64 %0, vcc, 0, %0, %10\n\t"
+            "v_addc_co_u32_e64 %1, vcc, 0, %1, %11"
+            : "+v"(c0), "+v"(c1), "=&s"(m0), "=&s"(m1), "=&s"(m2), "=&s"(m3), "=&s"(m4), "=&s"(m5), "=&s"(m6), "=&s"(m7),
+              "=&s"(m8), "=&s"(m9)
+            : "v"(r[b + 0]), "v"(r[b + 1]), "v"(r[b + 2]), "v"(r[b + 3]), "v"(r[b + 4]), "v"(r[b + 5]), "v"(r[b + 6]),
+              "v"(r[b + 7]), "v"(r[b + 8]), "v"(r[b + 9]), "v"(m)
+            : "vcc");
+    }
+    return pair_sum(c0 + c1);
 }
 
 struct Refreshed {
     int cnt;
     float tau;
+    int passes;   // search passes taken (read by the profiling build only)
+    unsigned t[4];   // profiling build: cycles of load / bracket / search / compaction
 };
 
-// Tighten tau of every token of the wavefront and compact the lists.  A token with >= k candidates
-// ends with between k and `target` of them (exactly k when target == k), all >= the new tau; every
-// dropped candidate is below k kept ones (ties: higher feature id).  Counts are over both lanes of
-// the token.  The search for tau brackets the k-th largest value between lo (count >= k) and hi
-// (count < k) and alternates interpolation on the counts with plain halving.
-__device__ __noinline__ Refreshed refresh_fast(List L, int k, int target, int cnt, float tau) {
-    const int total = cnt + __shfl_xor(cnt, 32);
+// Tighten tau of every token of the wavefront and compact the lists (slot i of this lane's list lives
+// at cv[32 i] / ci[32 i]).  A token with >= k candidates ends with between k and `target` of them
+// (exactly k when target == k), all >= the new tau; every dropped candidate is below k kept ones
+// (ties: higher feature id).  Counts are over both lanes of the token.  Empty slots are held as -inf, which
+// no candidate equals (pre-activations are finite).  The search for tau brackets the k-th largest value
+// between lo (count >= k) and hi (count < k); it alternates interpolation on the logarithm of the counts
+// (the upper tail of the candidates is close to exponential) with plain halving.  The compaction writes
+// every element to the current end of the kept prefix and advances the end only past kept elements, so it
+// has no branches.
+template <bool PROF>
+__device__ __attribute__((noinline)) Refreshed refresh_fast(lds_f32* cv, lds_u16* ci, int k, int target, int cnt, float tau) {
+    Refreshed out;
+    unsigned tp = PROF ? (unsigned)clock64() : 0u;
+#define S3_RT(I) if (PROF) { const unsigned now_ = (unsigned)clock64(); out.t[I] = now_ - tp; tp = now_; }
+    const int total = pair_sum(cnt);
     const bool active = total >= k;
     float r[CAPL];
     uint16_t ids[CAPL];
 #pragma unroll
     for (int i = 0; i < CAPL; ++i) {
-        float v = L.cv[32 * i];
-        ids[i] = L.ci[32 * i];
+        float v = cv[32 * i];
+        ids[i] = ci[32 * i];
         r[i] = i < cnt ? v : -INFINITY;
     }
+    if (PROF) asm volatile("" ::"v"(r[CAPL - 1]), "v"(ids[CAPL - 1]));
+    S3_RT(0)
     float mx = -INFINITY;
 #pragma unroll
     for (int i = 0; i < CAPL; ++i) mx = fmaxf(mx, r[i]);
-    mx = fmaxf(mx, __shfl_xor(mx, 32));
+    mx = pair_max(mx);
     float lo = tau;
     if (__any(active && !(tau > -INFINITY))) {    // no finite threshold yet: start from the smallest candidate
         float mn = INFINITY;
 #pragma unroll
-        for (int i = 0; i < CAPL; ++i) mn = fminf(mn, i < cnt ? r[i] : INFINITY);
-        mn = fminf(mn, __shfl_xor(mn, 32));
+        for (int i = 0; i < CAPL; ++i) mn = fminf(mn, r[i] > -INFINITY ? r[i] : INFINITY);
+        mn = pair_min(mn);
         if (!(tau > -INFINITY)) lo = mn;
     }
-    float hi = mx;
-    int clo = total, chi;
+    float hi = nextafterf(mx, INFINITY);          // exclusive upper end of the bracket: no candidate is >= hi
+    int clo = total, chi = 0;
     bool done = !active || clo <= target;
     bool split_failed = false;
-    {
-        chi = count_ge_regs(r, mx);
-        if (!done && chi >= k) { lo = mx; clo = chi; done = true; split_failed = true; }
-    }
-    const float want = 0.5f * (float)(k + target);
+    S3_RT(1)
+    const float lwant = __log2f(0.5f * (float)(k + target));
     bool interp = true;
+    int passes = 0;
     while (__any(!done)) {
-        float half_mid = 0.5f * lo + 0.5f * hi;
-        float t = fminf(fmaxf(((float)clo - want) / (float)(clo - chi), 0.125f), 0.875f);
+        ++passes;
+        const float llo = __log2f((float)clo), lhi = __log2f((float)max(chi, 1));
+        const float t = fminf(fmaxf((llo - lwant) / (llo - lhi), 0.0625f), 0.9375f);
         float mid = lo + (hi - lo) * t;
-        if (!interp || !(mid > lo && mid < hi)) mid = half_mid;
-        bool can = (mid > lo) && (mid < hi);
-        int cm = count_ge_regs(r, mid);
+        if (!interp || !(mid > lo && mid < hi)) mid = 0.5f * lo + 0.5f * hi;
+        const bool can = (mid > lo) && (mid < hi);
+        const int cm = count_ge_regs(r, mid);
         if (!done) {
             if (!can) { done = true; split_failed = true; }      // lo and hi are neighbouring floats
             else if (cm >= k) { lo = mid; clo = cm; if (clo <= target) done = true; }
@@ -124,66 +220,60 @@ __device__ __noinline__ Refreshed refresh_fast(List L, int k, int target, int cn
         }
         interp = !interp;
     }
-    bool tie = active && split_failed && clo > target;
-    int idcut = 0xFFFF;
-    if (__any(tie)) {     // every candidate in [lo, hi) equals lo: keep the tied ones with the lowest ids (rare)
+    S3_RT(2)
+    const bool tie = active && split_failed && clo > target;
+    lds_f32* wv_ = cv;
+    lds_u16* wi_ = ci;
+    if (!__any(tie)) {
+        const float cut = fmaxf(lo, -FLT_MAX);                   // empty slots never pass
+#pragma unroll
+        for (int i = 0; i < CAPL; ++i) {
+            const bool keep = r[i] >= cut;
+            *wv_ = r[i];
+            *wi_ = ids[i];
+            wv_ += keep ? 32 : 0;
+            wi_ += keep ? 32 : 0;
+        }
+    } else {      // some token: every candidate in [lo, hi) equals lo; keep its tied ones with the lowest ids (rare)
         int cgt = 0;
 #pragma unroll
         for (int i = 0; i < CAPL; ++i) cgt += (r[i] > lo) ? 1 : 0;
-        cgt += __shfl_xor(cgt, 32);
+        cgt = pair_sum(cgt);
         const int need = k - cgt;
         int ilo = -1, ihi = 0xFFFF;
         for (int it = 0; it < 16; ++it) {
-            int mid = (ilo + ihi) >> 1;
+            const int mid = (ilo + ihi) >> 1;
             int ce = 0;
 #pragma unroll
-            for (int i = 0; i < CAPL; ++i) ce += (r[i] == lo && i < cnt && (int)ids[i] <= mid) ? 1 : 0;
-            ce += __shfl_xor(ce, 32);
+            for (int i = 0; i < CAPL; ++i) ce += (r[i] == lo && (int)ids[i] <= mid) ? 1 : 0;
+            ce = pair_sum(ce);
             if (ce >= need) ihi = mid; else ilo = mid;
         }
-        idcut = ihi;
-    }
-    int jw = 0;
+        const int idcut = tie ? ihi : 0xFFFF;
+        const float cut = fmaxf(lo, -FLT_MAX);
 #pragma unroll
-    for (int i = 0; i < CAPL; ++i) {
-        float v = r[i];
-        bool keep = (v > lo || (v == lo && i < cnt)) && !(tie && v == lo && (int)ids[i] > idcut);
-        if (keep) {
-            L.cv[32 * jw] = v;
-            L.ci[32 * jw] = ids[i];
-            ++jw;
+        for (int i = 0; i < CAPL; ++i) {
+            const bool keep = r[i] >= cut && !(r[i] == lo && (int)ids[i] > idcut);
+            *wv_ = r[i];
+            *wi_ = ids[i];
+            wv_ += keep ? 32 : 0;
+            wi_ += keep ? 32 : 0;
         }
     }
-    Refreshed out;
-    out.cnt = jw;
+    S3_RT(3)
+#undef S3_RT
+    out.cnt = (int)(wv_ - cv) >> 5;
     out.tau = active ? lo : tau;
+    out.passes = passes;
     return out;
 }
 
-// fp32 -> three bf16 terms whose sum is the input exactly (8 significant bits each, by truncation)
-__device__ __forceinline__ uint2 split_bias(float b) {
-    unsigned u0 = __float_as_uint(b) & 0xFFFF0000u;
-    float r1 = b - __uint_as_float(u0);
-    unsigned u1 = __float_as_uint(r1) & 0xFFFF0000u;
-    float r2 = r1 - __uint_as_float(u1);
-    unsigned u2 = __float_as_uint(r2) & 0xFFFF0000u;
-    return make_uint2((u0 >> 16) | u1, u2 >> 16);
-}
-
-template <int DH, int ABL>
+template <int ABL>
 __global__ __launch_bounds__(kThreads) void sae_encode_topk_fast_kernel(EncParams p) {
-    constexpr int NS = DH / 16;
-    constexpr int RB = DH * ES;
-    constexpr int ROWB = RB + 16;          // W row + 16-byte pad that carries the bias terms
-    constexpr int VR = RB / 16;
-    constexpr int NV = kFT * VR / kThreads;
-    static_assert(kFT * VR % kThreads == 0, "a stage must divide evenly over the workgroup");
-
     extern __shared__ __align__(16) char smem[];
-    char* wst = smem;                                              // [2][kFT][ROWB]
-    lds_i32* vote = (lds_i32*)(smem + 2 * kFT * ROWB);             // [4] refresh votes, slot = step & 3
-    float* cval_all = (float*)(smem + 2 * kFT * ROWB + 16);        // [kWaves][2 CAPL][32]
-    uint16_t* cid_all = (uint16_t*)(cval_all + kWaves * 2 * CAPL * 32);
+    lds_char* const sm = (lds_char*)smem;                  // ring [kRing][32 rows][256 B] at 0, pieces xor-swizzled
+    const unsigned sm_a = (unsigned)(uintptr_t)sm;
+    const unsigned vote_a = sm_a + kOffVote;   // [4] refresh votes, slot = step & 3
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);      // wavefront index as a scalar: branches on it are uniform
@@ -193,206 +283,253 @@ __global__ __launch_bounds__(kThreads) void sae_encode_topk_fast_kernel(EncParam
     const int tok = tt * kTokWG + wv * 32 + n;
     const bool tok_ok = tok < p.T;
 
-    const char* wh = p.w + (size_t)head * p.n_feat * RB;
-    const float* bh = p.b + (size_t)head * p.n_feat;
-
     bf16x8 bfr[NS];
     {
         const char* row = p.x + ((size_t)head * p.T + (tok_ok ? tok : 0)) * RB;
 #pragma unroll
         for (int s = 0; s < NS; ++s) {
-            uint4 u = tok_ok ? *(const uint4*)(row + (16 * s + 8 * half) * ES) : make_uint4(0, 0, 0, 0);
+            uint4 u = tok_ok ? *(const uint4*)(row + (16 * s + 8 * half) * 2) : make_uint4(0, 0, 0, 0);
             bfr[s] = __builtin_bit_cast(bf16x8, u);
         }
     }
-    // B operand of the bias step: the low lane of a token multiplies the three bias terms by 1, the high lane by 0
-    const bf16x8 bones = __builtin_bit_cast(bf16x8, half ? make_uint4(0, 0, 0, 0) : make_uint4(0x3F803F80u, 0x00003F80u, 0, 0));
 
-    float* const wcv = cval_all + wv * 2 * CAPL * 32;             // this wavefront's value / id arrays
-    uint16_t* const wci = cid_all + wv * 2 * CAPL * 32;
-    lds_f32* const pv0 = (lds_f32*)(wcv + half * CAPL * 32 + n);   // this lane's list = its write pointers' origin
-    lds_u16* const pi0 = (lds_u16*)(wci + half * CAPL * 32 + n);
-    List L;
-    L.cv = pv0;
-    L.ci = pi0;
-    lds_f32* pv = pv0;
-    lds_u16* pi = pi0;
-    lds_f32* const pv_full = pv0 + (CAPL - kGuard) * 32;           // above this a group of 4 may not fit
-    lds_f32* const pv_soft = pv0 + p.soft * 32;                    // above this the lane asks for a voted refresh
+    // this lane's list: slot i of the values at pv0 + 32 i floats, of the ids at pi0 + 32 i
+    lds_f32* const pv0 = (lds_f32*)(sm + kOffVal) + (wv * 2 + half) * CAPL * 32 + n;
+    lds_u16* const pi0 = (lds_u16*)(sm + kOffId) + (wv * 2 + half) * CAPL * 32 + n;
+    const unsigned pv0a = (unsigned)(uintptr_t)pv0, pi0a = (unsigned)(uintptr_t)pi0;
+    unsigned pv = pv0a, pi = pi0a;                                 // write pointers (LDS byte addresses)
+    const unsigned pv_full = pv0a + (CAPL - kGuard) * 128;         // above this a group of 4 may not fit
+    const unsigned pv_soft = pv0a + (p.soft > 0 ? p.soft : CAPL) * 128;                  // above this the lane asks for a voted refresh
     float tau = (ABL & kNoHits) ? INFINITY : -INFINITY;
     const int k = p.k;
     const int loose = min(k + (k >> 3) + 2, CAPL - kGuard);
-    const int nst = (p.n_feat + kFT - 1) / kFT;
-    const int nfull = p.n_feat / kFT;                              // stages before this one have all kFT rows
+    const int nst = p.n_feat / kFT;                                // a multiple of 4
+    const bool late = wv >= kWaves / 2;
 
-    // global -> register -> LDS copy of one stage: NV 16-byte pieces per thread, wavefront 0 also one bias per lane
-    int goff[NV], loff[NV], grow[NV];
+    // ---- global -> LDS copy of one stage: wavefront w copies rows 4w .. 4w+3 (16 lanes per row); lane l
+    // writes piece l of the wavefront's 1 KB, which must hold column piece (l & 15) xor (row & 15) of its row.
+    // Every wavefront also copies the stage's 32 biases (lanes 32-63 repeat them) to the same place: the
+    // copies carry identical bytes, and each wavefront only has to wait for its own.
+    // Stage numbers past the end are clamped: the copy then lands in a ring slot that is not read any more.
+    const int crow = wv * 4 + (lane >> 4);
+    const char* const wsrc = p.w + (size_t)head * p.n_feat * RB;
+    const float* const bsrc = p.b + (size_t)head * p.n_feat;
+    const unsigned wlane = (unsigned)(crow * RB + (((lane & 15) ^ (crow & 15)) << 4));
+    const unsigned blane = (unsigned)(n * 4);
+#define S3_LOAD_STAGE(J, BUF)                                                                                \
+    do {                                                                                                     \
+        const int js_ = min((J), nst - 1);                                                                   \
+        __builtin_amdgcn_global_load_lds((glb_cvoid*)(wsrc + (size_t)js_ * kStageB + wlane),                 \
+                                         (lds_void*)(sm + (BUF) * kStageB + wv * 1024), 16, 0, 0);           \
+        __builtin_amdgcn_global_load_lds((glb_cvoid*)((const char*)(bsrc + js_ * kFT) + blane),              \
+                                         (lds_void*)(sm + kOffBias + (BUF) * kBiasB), 4, 0, 0);              \
+    } while (0)
+
+    // ---- fragment addresses: lane (row n, half h) reads column piece 2s + h of its row in K step s;
+    // its 16 accumulators are features q*8 + h*4 + 0..3 (q = 0..3) of the stage
+    unsigned xo[NS];
 #pragma unroll
-    for (int i = 0; i < NV; ++i) {
-        int v = tid + i * kThreads;
-        grow[i] = v / VR;
-        goff[i] = grow[i] * RB + (v % VR) * 16;
-        loff[i] = grow[i] * ROWB + (v % VR) * 16;
+    for (int s = 0; s < NS; ++s) xo[s] = sm_a + (unsigned)(n * RB + (((2 * s + half) ^ (n & 15)) << 4));
+    const unsigned ba = sm_a + (unsigned)(kOffBias + half * 16);
+
+    f32x16 acc = {};
+    // All LDS reads of a step in one statement that also waits for them: 4 x 16 B of biases, 8 x 16 B of W
+    // fragments of ring slot BUF, and the vote slot of the previous step.  Declares the step's fragment
+    // variables; S3_MFMAS consumes them (the bias vector is the first MFMA's C operand).
+#define S3_READS(BUF)                                                                                        \
+    f32x4 c0_, c1_, c2_, c3_;                                                                                \
+    u32x4 f0_, f1_, f2_, f3_, f4_, f5_, f6_, f7_;                                                            \
+    unsigned vt_;                                                                                            \
+    asm volatile(                                                                                            \
+        "ds_read_b128 %0, %13 offset:%23\n\t"                                                                \
+        "ds_read_b128 %1, %13 offset:%24\n\t"                                                                \
+        "ds_read_b128 %2, %13 offset:%25\n\t"                                                                \
+        "ds_read_b128 %3, %13 offset:%26\n\t"                                                                \
+        "ds_read_b128 %4, %14 offset:%27\n\t"                                                                \
+        "ds_read_b128 %5, %15 offset:%27\n\t"                                                                \
+        "ds_read_b128 %6, %16 offset:%27\n\t"                                                                \
+        "ds_read_b128 %7, %17 offset:%27\n\t"                                                                \
+        "ds_read_b128 %8, %18 offset:%27\n\t"                                                                \
+        "ds_read_b128 %9, %19 offset:%27\n\t"                                                                \
+        "ds_read_b128 %10, %20 offset:%27\n\t"                                                               \
+        "ds_read_b128 %11, %21 offset:%27\n\t"                                                               \
+        "ds_read_b32 %12, %22 offset:%28\n\t"                                                                \
+        "s_waitcnt lgkmcnt(0)"                                                                               \
+        : "=&v"(c0_), "=&v"(c1_), "=&v"(c2_), "=&v"(c3_), "=&v"(f0_), "=&v"(f1_), "=&v"(f2_), "=&v"(f3_),    \
+          "=&v"(f4_), "=&v"(f5_), "=&v"(f6_), "=&v"(f7_), "=&v"(vt_)                                         \
+        : "v"(ba), "v"(xo[0]), "v"(xo[1]), "v"(xo[2]), "v"(xo[3]), "v"(xo[4]), "v"(xo[5]), "v"(xo[6]),       \
+          "v"(xo[7]), "v"(vote_a), "n"((BUF) * kBiasB), "n"((BUF) * kBiasB + 32), "n"((BUF) * kBiasB + 64),      \
+          "n"((BUF) * kBiasB + 96), "n"((BUF) * kStageB), "n"((((BUF) + 3) & 3) * 4)                         \
+        : "memory");                                                                                         \
+    S3_T(1)
+#define S3_MFMAS()                                                                                           \
+    {                                                                                                        \
+        f32x16 ci_ = __builtin_shufflevector(__builtin_shufflevector(c0_, c1_, 0, 1, 2, 3, 4, 5, 6, 7),      \
+                                             __builtin_shufflevector(c2_, c3_, 0, 1, 2, 3, 4, 5, 6, 7),      \
+                                             0, 1, 2, 3, 4, 5, 6, 7, 8, 9, 10, 11, 12, 13, 14, 15);          \
+        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, f0_), bfr[0], ci_, 0, 0, 0); \
+        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, f1_), bfr[1], acc, 0, 0, 0); \
+        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, f2_), bfr[2], acc, 0, 0, 0); \
+        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, f3_), bfr[3], acc, 0, 0, 0); \
+        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, f4_), bfr[4], acc, 0, 0, 0); \
+        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, f5_), bfr[5], acc, 0, 0, 0); \
+        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, f6_), bfr[6], acc, 0, 0, 0); \
+        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, f7_), bfr[7], acc, 0, 0, 0); \
     }
-    // The stage loop is written with macros over plain local variables (no closures), so that every piece
-    // of state stays in registers.
-    //
-    // Two register sets (A, B): stage s travels in set s & 1, is requested two steps before it is used and
-    // written to LDS one step before, so a load has two whole steps to arrive.
-    uint4 wA0, wA1, wB0, wB1;
-    uint2 bA = make_uint2(0, 0), bB = make_uint2(0, 0);
-    wA1 = wB1 = make_uint4(0, 0, 0, 0);
-
-#define S3_GLOAD(J, W0, W1, BR)                                                                              \
-    do {                                                                                                     \
-        const int j_ = (J);                                                                                  \
-        const char* base_ = wh + (size_t)j_ * kFT * RB;                                                      \
-        if (j_ < nfull) { /* hot path: no predication */                                                     \
-            W0 = *(const uint4*)(base_ + goff[0]);                                                           \
-            if (NV > 1) W1 = *(const uint4*)(base_ + goff[NV - 1]);                                          \
-            if (wv == 0) BR = split_bias(bh[j_ * kFT + lane]);                                               \
-        } else { /* last, partial stage: missing rows are zero with bias -inf */                             \
-            const int left_ = p.n_feat - j_ * kFT;                                                           \
-            W0 = grow[0] < left_ ? *(const uint4*)(base_ + goff[0]) : make_uint4(0, 0, 0, 0);                \
-            if (NV > 1) W1 = grow[NV - 1] < left_ ? *(const uint4*)(base_ + goff[NV - 1]) : make_uint4(0, 0, 0, 0); \
-            if (wv == 0) BR = lane < left_ ? split_bias(bh[j_ * kFT + lane]) : make_uint2(0xFF80u, 0);       \
-        }                                                                                                    \
-    } while (0)
-
-#define S3_SSTORE(BUF, W0, W1, BR)                                                                           \
-    do {                                                                                                     \
-        char* base_ = wst + (BUF) * kFT * ROWB;                                                              \
-        *(uint4*)(base_ + loff[0]) = W0;                                                                     \
-        if (NV > 1) *(uint4*)(base_ + loff[NV - 1]) = W1;                                                    \
-        if (wv == 0) *(uint4*)(base_ + lane * ROWB + RB) = make_uint4(BR.x, BR.y, 0, 0);                     \
-    } while (0)
-
-    f32x16 acc0, acc1;
-    const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-
-#define S3_MMA(CUR)                                                                                          \
-    do {                                                                                                     \
-        if (ABL & kNoMfma) break;                                                                            \
-        const char* a0_ = wst + ((CUR) * kFT + n) * ROWB;                                                    \
-        const char* a1_ = a0_ + 32 * ROWB;                                                                   \
-        {   /* bias terms: same address for both lanes of a token */                                         \
-            uint4 g0_ = *(const uint4*)(a0_ + RB), g1_ = *(const uint4*)(a1_ + RB);                          \
-            acc0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, g0_), bones, zero, 0, 0, 0); \
-            acc1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, g1_), bones, zero, 0, 0, 0); \
-        }                                                                                                    \
-        _Pragma("unroll") for (int s = 0; s < NS; s += 2) {   /* two K steps at a time keeps few fragments live */ \
-            uint4 f00_ = *(const uint4*)(a0_ + 16 * half + 32 * s);                                          \
-            uint4 f10_ = *(const uint4*)(a1_ + 16 * half + 32 * s);                                          \
-            uint4 f01_ = *(const uint4*)(a0_ + 16 * half + 32 * s + 32);                                     \
-            uint4 f11_ = *(const uint4*)(a1_ + 16 * half + 32 * s + 32);                                     \
-            acc0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, f00_), bfr[s], acc0, 0, 0, 0); \
-            acc1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, f10_), bfr[s], acc1, 0, 0, 0); \
-            acc0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, f01_), bfr[s + 1], acc0, 0, 0, 0); \
-            acc1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, f11_), bfr[s + 1], acc1, 0, 0, 0); \
-        }                                                                                                    \
-    } while (0)
 
 #define S3_REFRESH(TARGET)                                                                                   \
     do {                                                                                                     \
-        Refreshed r_ = refresh_fast(L, k, (TARGET), (int)(pv - pv0) >> 5, tau);                              \
+        const unsigned t0_ = (ABL & kProfile) ? (unsigned)clock64() : 0u;                                    \
+        if (ABL & kProfile) napp += (pv - pv0a) >> 7;                                                        \
+        Refreshed r_ = refresh_fast<(ABL & kProfile) != 0>(pv0, pi0, k, (TARGET), (int)(pv - pv0a) >> 7, tau);                      \
+        if (ABL & kProfile) {                                                                                \
+            napp -= r_.cnt;                                                                                  \
+            prof[6] += (unsigned)clock64() - t0_;                                                            \
+            prof[7] += 1 + (r_.passes << 16);                                                                \
+            for (int i_ = 0; i_ < 4; ++i_) rprof[i_] += r_.t[i_];                                            \
+        }                                                                                                    \
         tau = r_.tau;                                                                                        \
-        pv = pv0 + r_.cnt * 32;                                                                              \
-        pi = pi0 + r_.cnt * 32;                                                                              \
+        pv = pv0a + r_.cnt * 128;                                                                            \
+        pi = pi0a + r_.cnt * 64;                                                                             \
     } while (0)
-
-#define S3_APPEND(H, A, IDV)                                                                                 \
-    if (H) {                                                                                                 \
-        *pv = (A);                                                                                           \
-        *pi = (uint16_t)(IDV);                                                                               \
-        pv += 32;                                                                                            \
-        pi += 32;                                                                                            \
+    // The compiler does not see that the compares below read MFMA results: the wait states that an 8-pass
+    // MFMA needs before a vector instruction may read its destination are spelled out.
+#define S3_MFMA_NOPS "s_nop 7\n\ts_nop 4\n\t"
+    // Hit masks of accumulators B0 .. B0+7 (one scalar 64-lane mask each), computed back to back so that the
+    // branches below wait for no vector compare.
+#define S3_MASKS8(B0, NOPS)                                                                                  \
+    asm(NOPS "v_cmp_gt_f32_e64 %0, %8, %16\n\t"                                                                 \
+        "v_cmp_gt_f32_e64 %1, %9, %16\n\t"                                                                   \
+        "v_cmp_gt_f32_e64 %2, %10, %16\n\t"                                                                  \
+        "v_cmp_gt_f32_e64 %3, %11, %16\n\t"                                                                  \
+        "v_cmp_gt_f32_e64 %4, %12, %16\n\t"                                                                  \
+        "v_cmp_gt_f32_e64 %5, %13, %16\n\t"                                                                  \
+        "v_cmp_gt_f32_e64 %6, %14, %16\n\t"                                                                  \
+        "v_cmp_gt_f32_e64 %7, %15, %16"                                                                      \
+        : "=s"(hm[(B0) + 0]), "=s"(hm[(B0) + 1]), "=s"(hm[(B0) + 2]), "=s"(hm[(B0) + 3]), "=s"(hm[(B0) + 4]), \
+          "=s"(hm[(B0) + 5]), "=s"(hm[(B0) + 6]), "=s"(hm[(B0) + 7])                                         \
+        : "v"(acc[(B0) + 0]), "v"(acc[(B0) + 1]), "v"(acc[(B0) + 2]), "v"(acc[(B0) + 3]), "v"(acc[(B0) + 4]), \
+          "v"(acc[(B0) + 5]), "v"(acc[(B0) + 6]), "v"(acc[(B0) + 7]), "v"(tau))
+    // Accumulator R (feature fb + 8 (R / 4) + R % 4): skipped by a scalar branch when no lane of the wavefront
+    // has a survivor; otherwise the lanes of its mask append (value, id), advance their write pointers and
+    // record in `full` whether a list got too long.  The workgroup runs with all lanes enabled here.
+#define S3_HIT(R)                                                                                            \
+    if (__builtin_expect(hm[R] != 0, 0)) {                                                                   \
+        unsigned t_;                                                                                         \
+        asm volatile("s_mov_b64 exec, %[m]\n\t"                                                              \
+                     "v_add_u32 %[t], %[c], %[fb]\n\t"                                                       \
+                     "ds_write_b32 %[pv], %[a]\n\t"                                                          \
+                     "ds_write_b16 %[pi], %[t]\n\t"                                                          \
+                     "v_add_u32 %[pv], 0x80, %[pv]\n\t"                                                      \
+                     "v_add_u32 %[pi], 64, %[pi]\n\t"                                                        \
+                     "v_cmp_gt_u32 vcc, %[pv], %[lim]\n\t"                                                   \
+                     "s_mov_b64 exec, -1\n\t"                                                                \
+                     "s_or_b64 %[full], %[full], vcc"                                                        \
+                     : [pv] "+v"(pv), [pi] "+v"(pi), [full] "+s"(full), [t] "=&v"(t_)                        \
+                     : [m] "s"(hm[R]), [a] "v"(acc[R]), [fb] "v"(fb), [c] "n"(8 * ((R) / 4) + (R) % 4),      \
+                       [lim] "v"(pv_full)                                                                    \
+                     : "vcc", "memory");                                                                     \
     }
-
-    // Compare/append of one group of 4 accumulators (features FB + 0..3): one uniform branch skips it when
-    // no lane of the wavefront has a survivor.  Every lane has >= kGuard free slots at the start of a group
-    // (checked after each group that appended).  The id base is made opaque inside the branch so that ids
-    // are formed only when something is appended.
-#define S3_GROUP(A0, A1, A2, A3, FB)                                                                         \
+    // Every lane has >= kGuard free slots at the start of a group of 4 accumulators.  The masks of later
+    // groups were taken with the threshold before a refresh: they may name candidates below the new one,
+    // which the next refresh drops.
+#define S3_GROUP(G)                                                                                          \
+    S3_HIT(4 * (G) + 0) S3_HIT(4 * (G) + 1) S3_HIT(4 * (G) + 2) S3_HIT(4 * (G) + 3)                          \
+    if (__builtin_expect(full != 0, 0)) {                                                                    \
+        S3_REFRESH(loose);                                                                                   \
+        full = 0;                                                                                            \
+    }
+    // Epilogue of stage ST in step JJ: refresh first if the workgroup voted for it in the previous step
+    // (the vote slot then holds this step's number), and cast a vote for the next step if a list is long.
+#define S3_EPILOGUE(ST, JJ, SLOT, VT)                                                                          \
     do {                                                                                                     \
-        const float a0_ = (A0), a1_ = (A1), a2_ = (A2), a3_ = (A3);                                          \
-        const bool h0_ = a0_ > tau, h1_ = a1_ > tau, h2_ = a2_ > tau, h3_ = a3_ > tau;                       \
-        if (__any(h0_ || h1_ || h2_ || h3_)) {                                                               \
-            unsigned idb_ = (FB);                                                                            \
-            asm volatile("" : "+v"(idb_));                                                                   \
-            S3_APPEND(h0_, a0_, idb_ + 0)                                                                    \
-            S3_APPEND(h1_, a1_, idb_ + 1)                                                                    \
-            S3_APPEND(h2_, a2_, idb_ + 2)                                                                    \
-            S3_APPEND(h3_, a3_, idb_ + 3)                                                                    \
-            if (__any(pv > pv_full)) S3_REFRESH(loose); /* emergency: a list may not take another group */   \
-        }                                                                                                    \
+        if (__builtin_expect(__builtin_amdgcn_readfirstlane((int)(VT)) == (JJ), 0)) S3_REFRESH(loose);       \
+        S3_T(8)                                                                                              \
+        const unsigned fb = (unsigned)((ST) * kFT + half * 4);                                               \
+        unsigned long long hm[16];                                                                           \
+        S3_MASKS8(0, S3_MFMA_NOPS);                                                                          \
+        S3_MASKS8(8, "");                                                                                    \
+        if (ABL & kProfile) asm volatile("" ::"s"(hm[0]), "s"(hm[15]));                                        \
+        S3_T(9)                                                                                              \
+        S3_GROUP(0) S3_GROUP(1) S3_GROUP(2) S3_GROUP(3)                                                      \
+        S3_T(10)                                                                                             \
+        if (__builtin_expect(__any(pv > pv_soft), 0)) lds_store_u32(vote_a + (SLOT) * 4, (unsigned)((JJ) + 1)); \
     } while (0)
+    unsigned long long full = 0;
+#define S3_T(I)                                                                                              \
+    if (ABL & kProfile) {                                                                                    \
+        const unsigned now_ = (unsigned)clock64();                                                           \
+        prof[I] += now_ - tprev;                                                                             \
+        tprev = now_;                                                                                        \
+    }
+    unsigned prof[12] = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+    unsigned rprof[4] = {0, 0, 0, 0};
+    unsigned napp = 0;     // candidates this lane appended and later dropped
+    unsigned tprev = (ABL & kProfile) ? (unsigned)clock64() : 0u;
+#define S3_BARRIER() stage_barrier<2 * (kAhead - 1)>()
 
-    // Epilogue of the stage whose first feature is F0; STEPNO = current step; VOTED: the workgroup agreed in
-    // the previous step to refresh now.
-#define S3_EPILOGUE(F0, STEPNO, VOTED)                                                                       \
-    do {                                                                                                     \
-        if (ABL & kNoEpilogue) {                                                                             \
-            asm volatile("" ::"v"(acc0[0]), "v"(acc1[0]), "v"(acc0[15]), "v"(acc1[15]));                     \
-            break;                                                                                           \
-        }                                                                                                    \
-        if (VOTED) S3_REFRESH(loose);                                                                        \
-        const unsigned fb_ = (unsigned)((F0) + half * 4);                                                    \
-        S3_GROUP(acc0[0], acc0[1], acc0[2], acc0[3], fb_ + 0);                                               \
-        S3_GROUP(acc0[4], acc0[5], acc0[6], acc0[7], fb_ + 8);                                               \
-        S3_GROUP(acc0[8], acc0[9], acc0[10], acc0[11], fb_ + 16);                                            \
-        S3_GROUP(acc0[12], acc0[13], acc0[14], acc0[15], fb_ + 24);                                          \
-        S3_GROUP(acc1[0], acc1[1], acc1[2], acc1[3], fb_ + 32);                                              \
-        S3_GROUP(acc1[4], acc1[5], acc1[6], acc1[7], fb_ + 40);                                              \
-        S3_GROUP(acc1[8], acc1[9], acc1[10], acc1[11], fb_ + 48);                                            \
-        S3_GROUP(acc1[12], acc1[13], acc1[14], acc1[15], fb_ + 56);                                          \
-        if (__any(pv > pv_soft) && lane == 0) vote[(STEPNO) & 3] = 1;                                        \
-    } while (0)
+    if (tid < 4) lds_store_u32(vote_a + tid * 4, 0xFFFFFFFFu);
+    S3_LOAD_STAGE(0, 0);
+    S3_LOAD_STAGE(1, 1);
+    S3_LOAD_STAGE(2, 2);
+    stage_barrier<0>();
 
-    // One step of the stage loop.  CUR = step & 1 is a literal (the loop is unrolled by two); LATE selects
-    // the order of MFMA and epilogue.  (WL*, BL) is the register set to load stage j + 2 into, (WS*, BS) the
-    // set whose stage j + 1 is written to LDS.
-#define S3_STEP(J, CUR, LATE, WL0, WL1, BL, WS0, WS1, BS)                                                    \
-    do {                                                                                                     \
-        const int js_ = (J);                                                                                 \
-        if (!(ABL & kNoLoads) && js_ + 2 < nst) S3_GLOAD(js_ + 2, WL0, WL1, BL);                             \
-        const int voted_ = (p.soft > 0 && js_ > 0) ? __builtin_amdgcn_readfirstlane(vote[(js_ - 1) & 3]) : 0; \
-        if (tid == 0 && js_ > 1) vote[(js_ - 2) & 3] = 0;                                                    \
-        if (!(LATE)) {                                                                                       \
-            S3_MMA(CUR);                                                                                     \
-            S3_EPILOGUE(js_* kFT, js_, voted_);                                                              \
-        } else {                                                                                             \
-            if (js_ > 0) S3_EPILOGUE((js_ - 1) * kFT, js_, voted_);                                          \
-            S3_MMA(CUR);                                                                                     \
-        }                                                                                                    \
-        if (!(ABL & kNoLoads) && js_ + 1 < nst) S3_SSTORE((CUR) ^ 1, WS0, WS1, BS);                          \
-        __syncthreads();                                                                                     \
-    } while (0)
-
-    if (tid < 4) vote[tid] = 0;
-    S3_GLOAD(0, wA0, wA1, bA);
-    S3_SSTORE(0, wA0, wA1, bA);
-    if (nst > 1) S3_GLOAD(1, wB0, wB1, bB);
-    __syncthreads();
-
-    // Wavefronts 0-3 (early) handle stage j in step j; wavefronts 4-7 (late) run the epilogue of stage j - 1
-    // first, so that the two wavefronts of a SIMD use the matrix pipe and the vector ALU at different times.
-    if (wv < kWaves / 2) {
-        for (int j = 0; j < nst; j += 2) {
-            S3_STEP(j, 0, false, wA0, wA1, bA, wB0, wB1, bB);
-            if (j + 1 < nst) S3_STEP(j + 1, 1, false, wB0, wB1, bB, wA0, wA1, bA);
-        }
+    // Step j runs the MFMAs of stage j (ring slot j & 3) and starts the copy of stage j + 3; at its end the
+    // wavefront waits for its copies of stage j + 1 (those of j + 2 and j + 3 stay in flight) and joins the
+    // barrier.  Wavefronts 0-3 handle the epilogue of stage j after the MFMAs of step j, wavefronts 4-7
+    // before the MFMAs of step j + 1.
+    if (!late) {
+#define S3_STEP(B)                                                                                           \
+    {                                                                                                        \
+        const int jj_ = j + (B);                                                                             \
+        S3_LOAD_STAGE(jj_ + kAhead, ((B) + kAhead) & 3);                                                     \
+        S3_T(0)                                                                                              \
+        S3_READS(B)                                                                                          \
+        S3_MFMAS()                                                                                           \
+        S3_T(2)                                                                                              \
+        S3_EPILOGUE(jj_, jj_, B, vt_);                                                                       \
+        S3_T(3)                                                                                              \
+        S3_BARRIER();                                                                                        \
+        S3_T(4)                                                                                              \
+    }
+        for (int j = 0; j < nst; j += 4) { S3_STEP(0) S3_STEP(1) S3_STEP(2) S3_STEP(3) }
+#undef S3_STEP
     } else {
-        for (int j = 0; j < nst; j += 2) {
-            S3_STEP(j, 0, true, wA0, wA1, bA, wB0, wB1, bB);
-            if (j + 1 < nst) S3_STEP(j + 1, 1, true, wB0, wB1, bB, wA0, wA1, bA);
-        }
-        S3_EPILOGUE((nst - 1) * kFT, nst, 0);
+#define S3_STEP(B)                                                                                           \
+    {                                                                                                        \
+        const int jj_ = j + (B);                                                                             \
+        S3_LOAD_STAGE(jj_ + kAhead, ((B) + kAhead) & 3);                                                     \
+        S3_T(0)                                                                                              \
+        S3_READS(B)                                                                                          \
+        if ((B) != 0 || j > 0) S3_EPILOGUE(jj_ - 1, jj_, B, vt_);                                            \
+        S3_T(3)                                                                                              \
+        S3_MFMAS()                                                                                           \
+        S3_T(2)                                                                                              \
+        S3_BARRIER();                                                                                        \
+        S3_T(4)                                                                                              \
+    }
+        for (int j = 0; j < nst; j += 4) { S3_STEP(0) S3_STEP(1) S3_STEP(2) S3_STEP(3) }
+#undef S3_STEP
+        S3_EPILOGUE(nst - 1, nst, 0, lds_load_u32(vote_a + 12));
+    }
+    stage_barrier<0>();          // no copy may be in flight when the workgroup ends; lists are complete
+    S3_REFRESH(k);
+    S3_T(5)
+    if (ABL & kProfile) {
+        napp += (pv - pv0a) >> 7;
+        for (int d = 32; d > 0; d >>= 1) napp += __shfl_xor((int)napp, d);
+        prof[5] = napp;    // appends of the whole wavefront (32 tokens)
+    }
+    if ((ABL & kProfile) && blockIdx.x == 0 && lane == 0 && (wv & 3) == 0) {
+        for (int i = 0; i < 12; ++i) s3_prof[(wv >> 2) * 12 + i] = prof[i];
+        if (wv == 0) for (int i = 0; i < 4; ++i) s3_prof[24 + i] = rprof[i];
     }
 
-    // exactly k per token, then a bitonic sort of each token's k candidates: lanes 0-31 sort token 2 it,
-    // lanes 32-63 token 2 it + 1; order (z descending, id ascending); lane e ends up with rank e.
-    S3_REFRESH(k);
-    const int cnt = (int)(pv - pv0) >> 5;
+    // bitonic sort of each token's k candidates: lanes 0-31 sort token 2 it, lanes 32-63 token 2 it + 1;
+    // order (z descending, id ascending); lane e ends up with rank e.
+    const int cnt = (int)(pv - pv0a) >> 7;
+    const lds_f32* const wcv = (lds_f32*)(sm + kOffVal) + wv * 2 * CAPL * 32;     // this wavefront's lists
+    const lds_u16* const wci = (lds_u16*)(sm + kOffId) + wv * 2 * CAPL * 32;
     int32_t* ids_h = p.ids + (size_t)head * p.T * k;
     float* vals_h = p.vals + (size_t)head * p.T * k;
     const int tok0 = tt * kTokWG + wv * 32;
@@ -427,38 +564,44 @@ __global__ __launch_bounds__(kThreads) void sae_encode_topk_fast_kernel(EncParam
     }
 }
 
-template <int DH, int ABL>
+template <int ABL>
 int launch_fast(EncParams p, hipStream_t st) {
-    constexpr int ROWB = DH * ES + 16;
-    const size_t lds = 2 * kFT * ROWB + 16 + (size_t)kWaves * 2 * CAPL * 32 * (sizeof(float) + sizeof(uint16_t));
-    auto kern = sae_encode_topk_fast_kernel<DH, ABL>;
+    auto kern = sae_encode_topk_fast_kernel<ABL>;
     static bool attr_set = false;
     if (!attr_set) {
-        S3_HIP(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+        S3_HIP(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes));
         attr_set = true;
     }
     p.tiles_per_head = (p.T + kTokWG - 1) / kTokWG;
     p.capt = 2 * CAPL;
-    hipLaunchKernelGGL(kern, dim3((unsigned)(p.n_heads * p.tiles_per_head)), dim3(kThreads), lds, st, p);
+    hipLaunchKernelGGL(kern, dim3((unsigned)(p.n_heads * p.tiles_per_head)), dim3(kThreads), kLdsBytes, st, p);
     S3_HIP(hipGetLastError());
     return S3_OK;
 }
 
 }  // namespace
 
-int s3_encode_fast_launch(EncParams p, int d_head, hipStream_t st) {
+bool s3_encode_fast_ok(int dtype, int d_head, int n_feat, int k) {
+    return dtype == S3_BF16 && d_head == DH && k <= 32 && n_feat % (4 * kFT) == 0;
+}
+
+int s3_encode_fast_launch(EncParams p, hipStream_t st) {
     static_assert(CAPL >= 32 + kGuard, "a lane must be able to hold k survivors and one more group");
+    static_assert(kLdsBytes <= 160 * 1024, "LDS budget of one CU");
     p.soft = env_int("S3_ENC_SOFT", 33);                           // list length that asks for a voted refresh (0 = off)
     if (p.soft < 0 || p.soft > CAPL - kGuard) return s3_fail(S3_EINVAL, "s3_sae_encode_topk: bad S3_ENC_SOFT");
-    if (d_head == 64) return launch_fast<64, 0>(p, st);
-    if (d_head != 128) return s3_fail(S3_EINVAL, "s3_sae_encode_topk: unsupported d_head %d", d_head);
     switch (p.ablate) {       // tuning builds: parts of the kernel compiled out (results are then meaningless)
-        case 0: return launch_fast<128, 0>(p, st);
-        case 1: return launch_fast<128, kNoHits>(p, st);
-        case 7: return launch_fast<128, kNoHits | kNoLoads | kNoEpilogue>(p, st);
-        case 11: return launch_fast<128, kNoHits | kNoLoads | kNoMfma>(p, st);
-        case 13: return launch_fast<128, kNoHits | kNoEpilogue | kNoMfma>(p, st);
-        case 15: return launch_fast<128, 15>(p, st);
+        case 0: return launch_fast<0>(p, st);
+        case 1: return launch_fast<kNoHits>(p, st);
+        case 16: return launch_fast<kProfile>(p, st);
+        case 17: return launch_fast<kProfile | kNoHits>(p, st);
     }
     return s3_fail(S3_EINVAL, "s3_sae_encode_topk: S3_ENC_ABLATE %d is not built", p.ablate);
+}
+
+// Tuning aid (not part of the public interface): phase cycle sums of the last S3_ENC_ABLATE=16/17 launch.
+extern "C" int s3_debug_profile(unsigned long long* out32) {
+    S3_HIP(hipDeviceSynchronize());
+    S3_HIP(hipMemcpyFromSymbol(out32, HIP_SYMBOL(s3_prof), sizeof(unsigned long long) * 32));
+    return S3_OK;
 }

@@ -35,14 +35,12 @@ struct EncParams {
     int32_t* ids;
     float* vals;
     int T, n_feat, k, n_heads, capt, tiles_per_head, ablate;
-    float opt_c;   // fast path: optimistic start tau0 = mean + opt_c * std (<= 0: start from -inf)
     int soft;      // fast path: list length per lane that asks for a workgroup-wide refresh (0: off)
-    int skew;      // fast path: 1 = odd wavefronts run half a stage late, 0 = wavefronts 4-7
-    unsigned long long* dbg;   // optional device counters for tuning (null in normal use)
 };
 
 int env_int(const char* name, int dflt);
-int s3_encode_fast_launch(EncParams p, int d_head, hipStream_t st);   // bf16, k <= 32
+bool s3_encode_fast_ok(int dtype, int d_head, int n_feat, int k);   // shapes the fast kernel is built for
+int s3_encode_fast_launch(EncParams p, hipStream_t st);
 
 // Workgroup -> (head, token tile).  Workgroups are dealt round-robin to the 8 XCDs (each with its own
 // L2), so consecutive tiles of one head are placed on the SAME XCD: they stream the same W_enc rows at
