@@ -141,3 +141,28 @@ def topb(W, span_len, top_b, nms=True):
 
 def threads() -> int:
     return int(lib().orc_threads())
+
+
+def score_dense(ids, qids, qvals, n_feat, max_freq=0):
+    """Position scores of Sec. 3.5 written token by token instead of posting by posting.
+
+    ids [H, L, k]: row t of head h holds the features active at position t; qids/qvals [H, nq, k].
+    S[t] = sum over heads h and features f active at (h, t) of IDF_h(f) * (sum of the query
+    activations of head h that name f); features with more than max_freq postings are skipped
+    (max_freq > 0).  Same sum as Index.score_accumulate over all heads, in another order: used where
+    building every head's postings on the host would take too long.
+    """
+    ids = np.asarray(ids)
+    H, L, k = ids.shape
+    S = np.zeros(L, np.float64)
+    for h in range(H):
+        freq = np.bincount(ids[h].reshape(-1), minlength=n_feat)
+        act = np.zeros(n_feat, np.float64)
+        np.add.at(act, np.asarray(qids[h]).reshape(-1), np.asarray(qvals[h], np.float64).reshape(-1))
+        w = np.zeros(n_feat, np.float64)
+        for fr in np.unique(freq[act != 0]):
+            if fr > 0 and not (max_freq > 0 and fr > max_freq):
+                sel = (freq == fr) & (act != 0)
+                w[sel] = act[sel] * idf(int(fr))
+        S += w[ids[h]].sum(axis=1)
+    return S

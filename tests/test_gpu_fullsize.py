@@ -1,0 +1,93 @@
+"""Parity at the full size of the benchmarked workload (Llama-8B shape: 256 (layer, head) pairs, chunks of 2048
+tokens, 16384 features, k = 32), in the launch configuration that bench.py times.  The oracle checks sampled
+rows of the encoder, whole inverted indexes of sampled heads, and every position score and span."""
+from concurrent.futures import ThreadPoolExecutor
+
+import numpy as np
+import pytest
+
+from oracle import s3_oracle as orc
+from paper_2601_17702_amd import synth
+from tests import parity
+
+pytestmark = pytest.mark.gpu
+W2 = synth.WORKLOADS["c2_llama8b"]
+
+
+def strided_ids(rng, rows, k, n_feat):
+    """[rows, k] distinct ids per row without a per-row shuffle: start + j * odd stride modulo a power of two."""
+    assert n_feat & (n_feat - 1) == 0
+    start = rng.integers(0, n_feat, (rows, 1), dtype=np.int64)
+    stride = rng.integers(0, n_feat // 2, (rows, 1), dtype=np.int64) * 2 + 1
+    return ((start + stride * np.arange(k, dtype=np.int64)) % n_feat).astype(np.int32)
+
+
+def test_encode_full_launch_sampled_rows():
+    import torch
+    import paper_2601_17702_amd as s3
+    w, H = W2, W2.n_heads
+    chunk = 3
+    with ThreadPoolExecutor(16) as ex:
+        parts = list(ex.map(lambda h: (synth.gen_keys(w, h, chunk), synth.gen_w_enc(w, h), synth.gen_b_enc(w, h)), range(H)))
+    x = np.stack([p[0] for p in parts]); W = np.stack([p[1] for p in parts]); b = np.stack([p[2] for p in parts])
+    ids = torch.empty((H, w.T, w.k), dtype=torch.int32, device="cuda")
+    vals = torch.empty((H, w.T, w.k), dtype=torch.float32, device="cuda")
+    s3.sae_encode_topk(parity.to_gpu(x, w.dtype), parity.to_gpu(W, w.dtype), parity.to_gpu(b, "fp32"), w.k, ids, vals)
+    torch.cuda.synchronize()
+    ids, vals = ids.cpu().numpy(), vals.cpu().numpy()
+    heads = [0, 7, 8, 137, 255]
+    toks = np.array([0, 1, 31, 32, 255, 256, 257, 1023, 1024, 1500, 2046, 2047])
+    ties, rows = parity.check_encode(ids[heads][:, toks], vals[heads][:, toks], x[heads][:, toks], W[heads], b[heads], w.k, w.dtype)
+    assert ties <= rows // 20
+    # properties of every row: distinct ids in range, values descending and non-negative
+    srt = np.sort(ids, axis=2)
+    assert srt.min() >= 0 and srt.max() < w.n_feat and np.all(np.diff(srt, axis=2) > 0)
+    assert np.all(np.diff(vals, axis=2) <= 0) and vals.min() >= 0
+
+
+def test_index_and_scores_full_size():
+    import torch
+    import paper_2601_17702_amd as s3
+    w, H = W2, W2.n_heads
+    rng = np.random.default_rng(5)
+    ids = strided_ids(rng, H * w.L, w.k, w.n_feat).reshape(H, w.L, w.k)
+    ids[:, ::3, 0] = 77                                       # one hot feature: a posting list of L/3 entries per head
+    for h in range(H):                                        # keep rows distinct where 77 was already present
+        dup = (ids[h, ::3, 1:] == 77).any(axis=1)
+        ids[h, ::3, 0][dup] = ids[h, ::3, 1][dup]
+        ids[h, ::3, 1][dup] = 77
+    index = s3.Index(H, w.n_feat, w.k, w.L)
+    for c in range(w.n_chunks):
+        index.append(torch.from_numpy(np.ascontiguousarray(ids[:, c * w.T:(c + 1) * w.T])).cuda(), base_pos=c * w.T)
+    index.finalize()
+    for h in (0, 100, 255):
+        ix = orc.Index(w.n_feat)
+        ix.append(ids[h], np.arange(w.L, dtype=np.int32))
+        off_o, pos_o = ix.csr()
+        off, pos = index.csr(h)
+        assert np.array_equal(off.cpu().numpy(), off_o) and np.array_equal(pos.cpu().numpy(), pos_o)
+    for h in range(0, H, 17):
+        off, _ = index.csr(h)
+        off = off.cpu().numpy()
+        assert off[0] == 0 and off[-1] == w.L * w.k and np.all(np.diff(off) >= 0)
+
+    qids = strided_ids(rng, H * w.nq, w.k, w.n_feat).reshape(H, w.nq, w.k)
+    qvals = (rng.random((H, w.nq, w.k)) * (rng.random((H, w.nq, w.k)) < 0.9)).astype(np.float32)
+    ws = torch.empty(index.score_workspace(w.L), dtype=torch.uint8, device="cuda")
+    for max_freq in (0, w.L // 4):
+        starts, scores, n, S_g = index.coactivate_score(torch.from_numpy(qids).cuda(), torch.from_numpy(qvals).cuda(), w.L,
+                                                        w.span_len, w.top_b, max_freq=max_freq, nms=True, ws=ws, want_scores=True)
+        torch.cuda.synchronize()
+        S = orc.score_dense(ids, qids, qvals, w.n_feat, max_freq=max_freq)
+        S_g = S_g.cpu().numpy()
+        assert np.allclose(S_g, S, rtol=1e-5, atol=1e-5 * S.max())
+        st_o, sc_o = orc.topb(orc.pool(S, w.span_len), w.span_len, w.top_b, nms=True)
+        n = int(n.item())
+        assert n == len(st_o)
+        st_g, sc_g = starts.cpu().numpy()[:n], scores.cpu().numpy()[:n]
+        assert np.allclose(sc_g, sc_o, rtol=1e-5)
+        # a start may differ from the oracle's only where two windows score within rounding of each other
+        Wp = orc.pool(S, w.span_len)
+        for a_, b_ in zip(st_g, st_o):
+            assert a_ == b_ or abs(Wp[a_] - Wp[b_]) <= 1e-5 * abs(Wp[b_])
+        assert np.all(np.abs(st_g[:, None] - st_g[None, :])[~np.eye(n, dtype=bool)] >= w.span_len)

@@ -327,3 +327,21 @@ def test_topb_hand_cases():
     assert st.tolist() == [0, 4]
     st, _ = orc.topb(W, 4, 100, nms=False)
     assert st.tolist() == list(range(7))
+
+
+def test_score_dense_equals_postings_form():
+    """The token-wise evaluation of the scoring equation (Sec. 3.5) and the postings traversal are the same sum."""
+    rng = np.random.default_rng(11)
+    H, L, k, n_feat, nq = 3, 200, 4, 37, 5
+    ids = np.stack([np.stack([rng.choice(n_feat, k, replace=False) for _ in range(L)]) for _ in range(H)]).astype(np.int32)
+    qids = np.stack([np.stack([rng.choice(n_feat, k, replace=False) for _ in range(nq)]) for _ in range(H)]).astype(np.int32)
+    qvals = rng.random((H, nq, k)).astype(np.float32)
+    for max_freq in (0, 25):
+        S = np.zeros(L)
+        for h in range(H):
+            ix = orc.Index(n_feat)
+            ix.append(ids[h], np.arange(L, dtype=np.int32))
+            ix.score_accumulate(qids[h], qvals[h], S, max_freq=max_freq)
+        D = orc.score_dense(ids, qids, qvals, n_feat, max_freq=max_freq)
+        assert np.allclose(S, D, rtol=1e-12, atol=1e-12)
+        assert max_freq == 0 or not np.allclose(D, orc.score_dense(ids, qids, qvals, n_feat, max_freq=0))
