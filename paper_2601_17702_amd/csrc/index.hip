@@ -326,6 +326,8 @@ struct s3_index {
     int n_heads, n_feat, k;
     int64_t max_tokens, tokens;
     bool finalized;
+    bool sorted;          // every posting list is in increasing position order (implicit, increasing positions only)
+    int64_t last_pos;     // position of the last appended row (implicit positions)
     Geometry g;
     IdxDev d;
     int32_t* pos_log;
@@ -336,7 +338,8 @@ struct s3_index {
 // Internal view for the scoring translation unit.
 void s3_index_view(const s3_index* idx, int* n_heads, int* n_feat, int* k, int64_t* tokens,
                                 const int32_t** offsets, int64_t* off_stride, const int32_t** positions,
-                                int64_t* pos_stride, bool* finalized) {
+                                int64_t* pos_stride, bool* finalized, bool* sorted) {
+    *sorted = idx->sorted;
     *n_heads = idx->n_heads; *n_feat = idx->n_feat; *k = idx->k; *tokens = idx->tokens;
     *offsets = idx->d.offsets; *off_stride = idx->d.off_stride;
     *positions = idx->d.positions; *pos_stride = idx->d.pos_stride; *finalized = idx->finalized;
@@ -356,7 +359,7 @@ int s3_index_create(int n_heads, int n_feat, int k, int64_t max_tokens, s3_index
     s3_index* ix = new (std::nothrow) s3_index();
     if (!ix) return s3_fail(S3_EHIP, "s3_index_create: out of host memory");
     ix->n_heads = n_heads; ix->n_feat = n_feat; ix->k = k; ix->max_tokens = max_tokens; ix->tokens = 0;
-    ix->finalized = false; ix->g = g;
+    ix->finalized = false; ix->sorted = true; ix->last_pos = -1; ix->g = g;
     IdxDev& d = ix->d;
     d.n_feat = n_feat; d.k = k; d.S = g.S; d.NB = g.NB; d.nbB = g.nbB; d.ptok = g.ptok; d.tile_post = g.tile_post;
     d.max_tiles = (int)((max_tokens + g.ptok - 1) / g.ptok);
@@ -401,6 +404,8 @@ int s3_index_reset(s3_index* idx) {
     if (!idx) return s3_fail(S3_EINVAL, "s3_index_reset: null index");
     idx->tokens = 0;
     idx->finalized = false;
+    idx->sorted = true;
+    idx->last_pos = -1;
     return S3_OK;
 }
 
@@ -418,8 +423,11 @@ int s3_index_append(s3_index* idx, const int32_t* ids, int T, const int32_t* pos
     const int k = idx->k, ptok = d.ptok, H = idx->n_heads;
     const int64_t r0 = idx->tokens;
     if (positions) {
+        idx->sorted = false;          // caller-given positions: order unknown to the host
         S3_HIP(hipMemcpyAsync(idx->pos_log + r0, positions, (size_t)T * 4, hipMemcpyDeviceToDevice, st));
     } else {
+        if ((int64_t)base_pos <= idx->last_pos) idx->sorted = false;
+        idx->last_pos = (int64_t)base_pos + T - 1;
         hipLaunchKernelGGL(idx_fill_positions_kernel, dim3((T + 255) / 256), dim3(256), 0, st, idx->pos_log + r0, T,
                            base_pos);
     }

@@ -25,7 +25,7 @@ static inline int s3_ceil_log2(unsigned v) {
 // Read-only view of an index for the scoring translation unit (defined in index.hip).
 void s3_index_view(const s3_index* idx, int* n_heads, int* n_feat, int* k, int64_t* tokens,
                    const int32_t** offsets, int64_t* off_stride, const int32_t** positions,
-                   int64_t* pos_stride, bool* finalized);
+                   int64_t* pos_stride, bool* finalized, bool* sorted);
 
 // ---- encoder internals shared by the generic and the fast kernel ----
 struct EncParams {

@@ -2,7 +2,8 @@
 // Sec. 3.5 "Adaptive Granularity" read as box pooling + fixed-length spans with NMS).
 //
 //   1. query weights   qw[h][f] = IDF_h(f) * sum of the query activations that name f
-//   2. postings gather S[t] += qw[h][f] for every t in I_h[f], all heads into one S
+//   2. postings gather S[t] += qw[h][f] for every t in I_h[f], all heads into one S (per block of positions
+//      in LDS; global atomics only for contexts longer than 8 blocks)
 //   3. span pooling    W[s] = S[s] + ... + S[s + len - 1]
 //   4. Top-B           greedy best window, optional suppression of overlapping windows
 //
@@ -36,6 +37,8 @@ struct ScoreArgs {
     Scal* sc;
     unsigned long long* qacc;        // [n_heads * n_feat] fixed-point sums, then doubles (query weights)
     unsigned long long* sfix;        // [L]
+    unsigned long long* part;        // [ngroup][L] partial sums of head groups (ngroup > 1)
+    int pb, npb, heads_per, ngroup, sorted;   // position blocks / head groups of the LDS scatter
     long long* wfix;                 // [nW]
     unsigned char* dead;             // [nW]
     long long* tmaxv;                // [ntile]
@@ -139,6 +142,103 @@ __global__ __launch_bounds__(256) void sc_scatter_kernel(ScoreArgs a) {
     }
 }
 
+// Postings gather with the scores of one block of positions held in LDS.
+// Workgroup (b, g) owns positions [b * pb, (b + 1) * pb) and the heads of group g: it walks every posting list
+// of those heads that has a non-zero weight and adds the postings that fall into its block with LDS atomics
+// (64-bit fixed point, so the order of the additions does not matter), then stores the block: into S when there
+// is one head group, else into that group's partial array (summed by sc_reduce_kernel).  No global atomics.
+// A wavefront takes 64 features at a time: lane l fetches weight and list bounds of feature l, then the lists
+// are walked four at a time (lanes over postings) so that four independent loads are in flight.
+// Lists are sorted by position when the index was fed increasing implicit positions; long lists are then
+// narrowed to the block by a per-lane binary search first.
+constexpr int kScatterThreads = 1024;
+constexpr int kMaxPB = 16384;
+
+__device__ __forceinline__ int lower_bound_pos(const int32_t* pos, int b, int e, int64_t key) {
+    while (b < e) {
+        int m = b + ((e - b) >> 1);
+        if ((int64_t)pos[m] < key) b = m + 1; else e = m;
+    }
+    return b;
+}
+
+__global__ __launch_bounds__(kScatterThreads) void sc_scatter_lds_kernel(ScoreArgs a) {
+    extern __shared__ unsigned long long sblk[];
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int64_t p0 = (int64_t)blockIdx.x * a.pb;
+    const int64_t p1 = p0 + a.pb < a.L ? p0 + a.pb : a.L;
+    const unsigned span = (unsigned)(p1 - p0);
+    for (int i = tid; i < a.pb; i += kScatterThreads) sblk[i] = 0ull;
+    __syncthreads();
+    const double scale = ldexp(1.0, exp_s(a.sc, a.hb));
+    const int h0 = blockIdx.y * a.heads_per, h1 = min(a.n_heads, h0 + a.heads_per);
+    for (int h = h0; h < h1; ++h) {
+        const int32_t* off = a.offsets + (size_t)h * a.off_stride;
+        const int32_t* pos = a.positions + (size_t)h * a.pos_stride;
+        const unsigned long long* qw = a.qacc + (size_t)h * a.n_feat;
+        for (int f0 = wave * 64; f0 < a.n_feat; f0 += (kScatterThreads / 64) * 64) {
+            const int f = f0 + lane;
+            unsigned long long wf = 0;
+            int b = 0, e = 0;
+            if (f < a.n_feat) {
+                const double w = __longlong_as_double((long long)qw[f]);
+                if (w > 0.0) wf = (unsigned long long)llrint(w * scale);
+                if (wf) {
+                    b = off[f];
+                    e = off[f + 1];
+                    if (a.sorted && a.npb > 1 && e - b > 128) {
+                        b = lower_bound_pos(pos, b, e, p0);
+                        e = lower_bound_pos(pos, b, e, p1);
+                    }
+                }
+            }
+            unsigned long long m = __ballot(e > b);
+            while (m) {
+                int it[4], bb[4], ee[4];
+                unsigned long long ww[4];
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    it[j] = m ? (int)__builtin_ctzll(m) : -1;
+                    if (m) m &= m - 1;
+                    const int src = it[j] < 0 ? 0 : it[j];
+                    bb[j] = __builtin_amdgcn_readlane(b, src);
+                    ee[j] = it[j] < 0 ? bb[j] : __builtin_amdgcn_readlane(e, src);
+                    const unsigned lo = __builtin_amdgcn_readlane((unsigned)wf, src);
+                    const unsigned hi = __builtin_amdgcn_readlane((unsigned)(wf >> 32), src);
+                    ww[j] = ((unsigned long long)hi << 32) | lo;
+                }
+                int32_t pp[4];
+#pragma unroll
+                for (int j = 0; j < 4; ++j) pp[j] = bb[j] + lane < ee[j] ? pos[bb[j] + lane] : -1;
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const unsigned r = (unsigned)((int64_t)pp[j] - p0);
+                    if (pp[j] >= 0 && r < span) atomicAdd(&sblk[r], ww[j]);
+                }
+#pragma unroll
+                for (int j = 0; j < 4; ++j)     // rest of a long list
+                    for (int q = bb[j] + 64 + lane; q < ee[j]; q += 64) {
+                        const int32_t pq = pos[q];
+                        const unsigned r = (unsigned)((int64_t)pq - p0);
+                        if (pq >= 0 && r < span) atomicAdd(&sblk[r], ww[j]);
+                    }
+            }
+        }
+    }
+    __syncthreads();
+    unsigned long long* dst = a.ngroup > 1 ? a.part + (size_t)blockIdx.y * a.L : a.sfix;
+    for (int64_t i = tid; i < (int64_t)span; i += kScatterThreads) dst[p0 + i] = sblk[i];
+}
+
+__global__ __launch_bounds__(256) void sc_reduce_kernel(ScoreArgs a) {
+    for (int64_t t = (int64_t)blockIdx.x * 256 + threadIdx.x; t < a.L; t += (int64_t)gridDim.x * 256) {
+        unsigned long long s = 0;
+        for (int g = 0; g < a.ngroup; ++g) s += a.part[(size_t)g * a.L + t];
+        a.sfix[t] = s;
+    }
+}
+
 constexpr int kRun = 32;   // consecutive windows per thread (sliding sum, exact in integers)
 
 __global__ __launch_bounds__(256) void sc_pool_kernel(ScoreArgs a) {
@@ -233,7 +333,8 @@ __global__ __launch_bounds__(kTileW) void sc_topb_kernel(ScoreArgs a) {
 }
 
 struct Layout {
-    size_t sc, qacc, sfix, wfix, dead, tmaxv, tmaxi, total;
+    size_t sc, qacc, sfix, wfix, dead, tmaxv, tmaxi, part, total;
+    int pb, npb, heads_per, ngroup;   // LDS scatter geometry (npb == 0: the global-atomic scatter is used)
 };
 
 Layout layout(int n_heads, int n_feat, int64_t L) {
@@ -248,6 +349,18 @@ Layout layout(int n_heads, int n_feat, int64_t L) {
     l.dead = take((size_t)L);
     l.tmaxv = take(ntile * 8);
     l.tmaxi = take(ntile * 4);
+    // position blocks of at most kMaxPB scores (128 KB of LDS); enough head groups for about 512 workgroups
+    l.pb = (int)(L < kMaxPB ? (L + 63) / 64 * 64 : kMaxPB);
+    const int64_t npb = (L + l.pb - 1) / l.pb;
+    l.npb = npb <= 8 ? (int)npb : 0;
+    l.heads_per = 1; l.ngroup = 1; l.part = o;
+    if (l.npb) {
+        int want = 512 / l.npb;
+        int groups = n_heads < want ? n_heads : (want < 1 ? 1 : want);
+        l.heads_per = (n_heads + groups - 1) / groups;
+        l.ngroup = (n_heads + l.heads_per - 1) / l.heads_per;
+        if (l.ngroup > 1) l.part = take((size_t)l.ngroup * L * 8);
+    }
     l.total = o;
     return l;
 }
@@ -259,8 +372,8 @@ extern "C" size_t s3_coactivate_score_workspace(const s3_index* idx, int64_t n_p
     int n_heads, n_feat, k;
     int64_t tokens, os, ps;
     const int32_t *off, *pos;
-    bool fin;
-    s3_index_view(idx, &n_heads, &n_feat, &k, &tokens, &off, &os, &pos, &ps, &fin);
+    bool fin, sorted;
+    s3_index_view(idx, &n_heads, &n_feat, &k, &tokens, &off, &os, &pos, &ps, &fin, &sorted);
     return layout(n_heads, n_feat, n_positions).total;
 }
 
@@ -276,8 +389,9 @@ extern "C" int s3_coactivate_score(const s3_index* idx, const int32_t* qids, con
         return s3_fail(S3_EINVAL, "s3_coactivate_score: n_positions %lld out of range", (long long)n_positions);
     ScoreArgs a;
     int64_t tokens;
-    bool fin;
-    s3_index_view(idx, &a.n_heads, &a.n_feat, &a.k, &tokens, &a.offsets, &a.off_stride, &a.positions, &a.pos_stride, &fin);
+    bool fin, sorted;
+    s3_index_view(idx, &a.n_heads, &a.n_feat, &a.k, &tokens, &a.offsets, &a.off_stride, &a.positions, &a.pos_stride, &fin,
+                  &sorted);
     if (!fin) return s3_fail(S3_ESTATE, "s3_coactivate_score: index not finalized");
     if ((int64_t)nq * a.k > (1 << 20)) return s3_fail(S3_EINVAL, "s3_coactivate_score: nq * k %lld > 2^20", (long long)nq * a.k);
     const Layout l = layout(a.n_heads, a.n_feat, n_positions);
@@ -299,6 +413,8 @@ extern "C" int s3_coactivate_score(const s3_index* idx, const int32_t* qids, con
     a.dead = (unsigned char*)(base + l.dead);
     a.tmaxv = (long long*)(base + l.tmaxv);
     a.tmaxi = (int*)(base + l.tmaxi);
+    a.part = (unsigned long long*)(base + l.part);
+    a.pb = l.pb; a.npb = l.npb; a.heads_per = l.heads_per; a.ngroup = l.ngroup; a.sorted = sorted ? 1 : 0;
     a.ntile = (int)((a.nW + kTileW - 1) / kTileW);
     a.scores_out = scores_out; a.span_start = span_start; a.span_score = span_score; a.n_found = n_found;
 
@@ -312,7 +428,19 @@ extern "C" int s3_coactivate_score(const s3_index* idx, const int32_t* qids, con
         hipLaunchKernelGGL(sc_qacc_kernel, dim3(blocks(npairs, 256)), dim3(256), 0, st, a);
         const size_t nhf = (size_t)a.n_heads * a.n_feat;
         hipLaunchKernelGGL(sc_qw_kernel, dim3(blocks(nhf, 256)), dim3(256), 0, st, a);
-        hipLaunchKernelGGL(sc_scatter_kernel, dim3((unsigned)((nhf + 3) / 4)), dim3(256), 0, st, a);
+        if (a.npb) {
+            static bool attr_set = false;
+            if (!attr_set) {
+                S3_HIP(hipFuncSetAttribute((const void*)sc_scatter_lds_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                           kMaxPB * 8));
+                attr_set = true;
+            }
+            hipLaunchKernelGGL(sc_scatter_lds_kernel, dim3((unsigned)a.npb, (unsigned)a.ngroup), dim3(kScatterThreads),
+                               (size_t)a.pb * 8, st, a);
+            if (a.ngroup > 1) hipLaunchKernelGGL(sc_reduce_kernel, dim3(blocks((size_t)a.L, 256)), dim3(256), 0, st, a);
+        } else {
+            hipLaunchKernelGGL(sc_scatter_kernel, dim3((unsigned)((nhf + 3) / 4)), dim3(256), 0, st, a);
+        }
     }
     hipLaunchKernelGGL(sc_pool_kernel, dim3(blocks((size_t)a.L, 256)), dim3(256), 0, st, a);
     hipLaunchKernelGGL(sc_tilemax_kernel, dim3(a.ntile), dim3(kTileW), 0, st, a);
