@@ -5,16 +5,20 @@
 // places per posting: nothing coalesces.  The build is therefore a two-level (most-significant
 // digit first) stable counting sort whose every global write is a contiguous run:
 //
-//   append   : each tile of <= 8192 postings (<= 8192/k tokens of one head) is sorted in LDS by
+//   append   : each tile of <= 8192 postings (<= 8192/k tokens of one head) is split in LDS by
 //              the feature's coarse bucket (f >> S, at most 256 buckets) and written out as one
 //              contiguous tile of packed (row << S | f & mask) words, plus a small table of
 //              (offset, count) per (bucket, tile).  The order inside a bucket stays the append
 //              order (stable), so positions inside a posting list come out ascending.
-//   finalize : per (head, bucket) the pieces of all tiles are gathered in tile order, sorted in
+//   finalize : per (head, bucket) the pieces of all tiles are gathered in tile order, split in
 //              LDS by the low feature bits (stable again) and written to their final place in the
 //              CSR; the per-feature counts of the bucket give offsets[].
 //
-// All ranks come from prefix sums over fixed thread orders: no atomics decide a position, so the
+// Both splits are one pass of a ballot-based multi-way split: the lanes of a wavefront that hold the same
+// digit find each other with one ballot per digit bit, per-wavefront counters and one block-wide prefix sum
+// give every entry its rank.
+//
+// All ranks come from prefix sums over fixed lane and wavefront orders: no atomics decide a position, so the
 // CSR is bit-identical from run to run and independent of how the stream was chunked.
 #include "s3_common.h"
 
@@ -23,11 +27,7 @@
 namespace {
 
 constexpr int kTilePost = 8192;       // postings per partition tile (upper bound)
-constexpr int kPartThreads = 256;
-constexpr int kSortThreads = 1024;
-constexpr int kSortCap = 16384;       // entries sorted per round in the bucket pass
-constexpr int kKeyRowBits = 13;       // tile-local key: bucket << 21 | f_lo << 13 | row_in_tile
-constexpr int kKeyBucketShift = 21;
+constexpr int kSortCap = 8192;        // entries split per round in the bucket pass
 
 struct IdxDev {
     uint32_t* inter;      // [n_heads][max_tiles * tile_post] packed (row << S | f_lo), bucket-sorted per tile
@@ -40,8 +40,6 @@ struct IdxDev {
     int64_t inter_stride, piece_stride, off_stride, pos_stride;
     int n_feat, k, S, NB, nbB, ptok, tile_post, max_tiles;
 };
-
-__device__ __forceinline__ int padi(int i) { return i + (i >> 5); }
 
 // Exclusive prefix sum of one int per thread over the block, in thread order.
 template <int NT>
@@ -67,75 +65,117 @@ __device__ __forceinline__ int block_excl_scan(int v, int* wsum, int& total) {
     return base + x - v;
 }
 
-// Stable LSD sort of the NT * E words in `a` (padded indexing) on key bits [bit_lo, bit_lo + nbits),
-// one bit per pass.  Thread t owns words [t E, (t + 1) E); ranks are prefix sums in that order.
-// Returns the buffer that holds the result.  Slots past the real entries must hold 0xFFFFFFFF.
-template <int NT>
-__device__ uint32_t* bitsplit_sort(uint32_t* a, uint32_t* b, int E, int bit_lo, int nbits, int* wsum) {
-    const int start = threadIdx.x * E;
-    for (int bit = bit_lo; bit < bit_lo + nbits; ++bit) {
-        int z = 0;
-        for (int i = 0; i < E; ++i) z += ((a[padi(start + i)] >> bit) & 1u) ? 0 : 1;
-        int tz;
-        int rz = block_excl_scan<NT>(z, wsum, tz);
-        int ro = tz + (start - rz);
-        for (int i = 0; i < E; ++i) {
-            uint32_t key = a[padi(start + i)];
-            int d = ((key >> bit) & 1u) ? ro++ : rz++;
-            b[padi(d)] = key;
-        }
-        __syncthreads();
-        uint32_t* t = a; a = b; b = t;
+// Lanes of the wavefront whose (valid) key has the same low `nbits` bits as this lane's: one ballot per bit.
+__device__ __forceinline__ unsigned long long same_key_lanes(unsigned key, int nbits, bool valid) {
+    unsigned long long p = __ballot(valid);
+    for (int bit = 0; bit < nbits; ++bit) {
+        const bool one = (key >> bit) & 1u;
+        const unsigned long long b = __ballot(valid && one);
+        p &= one ? b : ~b;
     }
-    return a;
+    return valid ? p : 0ull;
 }
 
-// One tile of <= tile_post postings of one head: sort by bucket, write the tile and its piece table.
-// `src` is the first row of tile `tile0` (row stride k, head stride head_stride elements).
-__global__ __launch_bounds__(kPartThreads) void idx_partition_kernel(const int32_t* src, int64_t head_stride,
-                                                                     int rows_avail, int tile0, IdxDev d) {
-    __shared__ uint32_t bufa[kTilePost + kTilePost / 32 + 8];
-    __shared__ uint32_t bufb[kTilePost + kTilePost / 32 + 8];
-    __shared__ int wsum[kPartThreads / 64];
-    __shared__ int bstart[256], bend[256];
+// Stable multi-way split of up to kWaves * kRounds * 64 keyed entries by a digit of at most 8 bits.
+// Wavefront w owns the entries [w seg, (w + 1) seg) in rounds of 64 (lane order = entry order).  Inside a round
+// the lanes that share a digit find each other with ballots; the first of them adds their number to the
+// wavefront's own counter row, so no atomics are needed and the order of equal digits is the entry order.
+//   count   : cnt[w][digit] += lanes with that digit                      (split_count)
+//   scan    : exclusive prefix over (digit major, wavefront minor)        (split_scan)
+//   rank    : cnt[w][digit] (now a running base) + lanes before me        (split_rank)
+constexpr int kSplitThreads = 1024;
+constexpr int kSplitWaves = kSplitThreads / 64;
+constexpr int kSplitRounds = 8;          // 16 wavefronts x 8 rounds x 64 lanes = 8192 entries per pass
 
-    const int tid = threadIdx.x, head = blockIdx.y;
+__device__ __forceinline__ void split_count(int* cnt_row, unsigned digit, unsigned long long peers, int lane) {
+    if (peers && (peers & ((1ull << lane) - 1ull)) == 0) cnt_row[digit] += __popcll(peers);
+}
+
+// cnt: [kSplitWaves][nd] counts -> running bases; dstart[d] / dcount[d]: first rank and number of entries of digit d
+__device__ __forceinline__ void split_scan(int* cnt, int nd, int* dstart, int* dcount, int* wsum) {
+    const int tid = threadIdx.x;
+    constexpr int per = kSplitWaves * 256 / kSplitThreads;     // 4 entries per thread when nd = 256
+    // entry e = d * kSplitWaves + w; thread t owns e = per t .. per t + per - 1 (one digit: per divides kSplitWaves)
+    const int d = tid * per / kSplitWaves, w0 = tid * per % kSplitWaves;
+    int v[per], s = 0;
+#pragma unroll
+    for (int j = 0; j < per; ++j) {
+        v[j] = d < nd ? cnt[(w0 + j) * nd + d] : 0;
+        s += v[j];
+    }
+    int tot;
+    int ex = block_excl_scan<kSplitThreads>(s, wsum, tot);
+    if (d < nd) {
+        int run = ex;
+#pragma unroll
+        for (int j = 0; j < per; ++j) {
+            cnt[(w0 + j) * nd + d] = run;
+            run += v[j];
+        }
+    }
+    // the kSplitWaves / per threads of a digit are adjacent lanes: their sum is the digit's count
+    int dc = s;
+#pragma unroll
+    for (int o = 1; o < kSplitWaves / per; o <<= 1) dc += __shfl_xor(dc, o);
+    if (d < nd && w0 == 0) { dstart[d] = ex; dcount[d] = dc; }
+    __syncthreads();
+}
+
+__device__ __forceinline__ int split_rank(int* cnt_row, unsigned digit, unsigned long long peers, int lane) {
+    int r = 0;
+    if (peers) r = cnt_row[digit] + __popcll(peers & ((1ull << lane) - 1ull));
+    if (peers && (peers & ((1ull << lane) - 1ull)) == 0) cnt_row[digit] = r + __popcll(peers);
+    return r;
+}
+
+// One tile of <= tile_post postings of one head: split by bucket, write the tile and its piece table.
+// `src` is the first row of tile `tile0` (row stride k, head stride head_stride elements).
+__global__ __launch_bounds__(kSplitThreads) void idx_partition_kernel(const int32_t* src, int64_t head_stride,
+                                                                      int rows_avail, int tile0, IdxDev d) {
+    __shared__ int cnt[kSplitWaves * 256];
+    __shared__ uint32_t stage[kTilePost];
+    __shared__ int wsum[kSplitWaves];
+    __shared__ int bstart[256], bcount[256];
+
+    const int tid = threadIdx.x, lane = tid & 63, head = blockIdx.y;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int tile = tile0 + blockIdx.x;
     const int nrows = min(d.ptok, rows_avail - (int)blockIdx.x * d.ptok);
     const int n = nrows * d.k;
     const int32_t* s = src + (size_t)head * head_stride + (size_t)blockIdx.x * d.ptok * d.k;
-    const int E = (n + kPartThreads - 1) / kPartThreads;
     const uint32_t mask = (1u << d.S) - 1u;
-
-    for (int i = tid; i < E * kPartThreads; i += kPartThreads) {
-        uint32_t key = 0xFFFFFFFFu;
-        if (i < n) {
-            uint32_t id = (uint32_t)s[i];
-            key = ((id >> d.S) << kKeyBucketShift) | ((id & mask) << kKeyRowBits) | (uint32_t)(i / d.k);
-        }
-        bufa[padi(i)] = key;
-    }
-    if (tid < 256) { bstart[tid] = 0; bend[tid] = 0; }
-    __syncthreads();
-    uint32_t* sorted = bitsplit_sort<kPartThreads>(bufa, bufb, E, kKeyBucketShift, d.nbB, wsum);
-
-    uint32_t* out = d.inter + (size_t)head * d.inter_stride + (size_t)tile * d.tile_post;
     const uint32_t row0 = (uint32_t)tile * (uint32_t)d.ptok;
-    for (int i = tid; i < n; i += kPartThreads) {
-        uint32_t key = sorted[padi(i)];
-        int bk = (int)(key >> kKeyBucketShift);
-        int prev = i > 0 ? (int)(sorted[padi(i - 1)] >> kKeyBucketShift) : -1;
-        if (bk != prev) {
-            bstart[bk] = i;
-            if (prev >= 0) bend[prev] = i;
-        }
-        if (i == n - 1) bend[bk] = n;
-        out[i] = ((row0 + (key & ((1u << kKeyRowBits) - 1u))) << d.S) | ((key >> kKeyRowBits) & mask);
+    const int nd = 1 << d.nbB;
+
+    for (int i = tid; i < kSplitWaves * nd; i += kSplitThreads) cnt[i] = 0;
+    __syncthreads();
+    int* row = cnt + wave * nd;
+    uint32_t word[kSplitRounds];
+    unsigned dig[kSplitRounds];
+    unsigned long long peers[kSplitRounds];
+#pragma unroll
+    for (int r = 0; r < kSplitRounds; ++r) {
+        const int i = (wave * kSplitRounds + r) * 64 + lane;
+        const bool valid = i < n;
+        const uint32_t id = valid ? (uint32_t)s[i] : 0u;
+        dig[r] = min(id >> d.S, (uint32_t)(nd - 1));     // ids are < n_feat by contract; never index past the counters
+        word[r] = ((row0 + (uint32_t)(i / d.k)) << d.S) | (id & mask);
+        peers[r] = same_key_lanes(dig[r], d.nbB, valid);
+        split_count(row, dig[r], peers[r], lane);
     }
     __syncthreads();
+    split_scan(cnt, nd, bstart, bcount, wsum);
+#pragma unroll
+    for (int r = 0; r < kSplitRounds; ++r) {
+        const int rk = split_rank(row, dig[r], peers[r], lane);
+        if (peers[r]) stage[rk] = word[r];
+    }
+    __syncthreads();
+    uint32_t* out = d.inter + (size_t)head * d.inter_stride + (size_t)tile * d.tile_post;
+    for (int i = tid; i < n; i += kSplitThreads) out[i] = stage[i];
     uint32_t* pc = d.piece + (size_t)head * d.piece_stride;
-    for (int b = tid; b < d.NB; b += kPartThreads)
-        pc[(size_t)b * d.max_tiles + tile] = ((uint32_t)bstart[b] << 16) | (uint32_t)(bend[b] - bstart[b]);
+    for (int b = tid; b < d.NB; b += kSplitThreads)
+        pc[(size_t)b * d.max_tiles + tile] = ((uint32_t)bstart[b] << 16) | (uint32_t)bcount[b];
 }
 
 __global__ __launch_bounds__(256) void idx_totals_kernel(IdxDev d, int n_tiles) {
@@ -163,24 +203,29 @@ __global__ __launch_bounds__(256) void idx_bucket_scan_kernel(IdxDev d) {
     }
 }
 
-// One (head, bucket): gather its pieces in tile order, sort by the low feature bits, write the CSR.
-__global__ __launch_bounds__(kSortThreads) void idx_bucket_sort_kernel(IdxDev d, int n_tiles) {
+// One (head, bucket): gather its pieces in tile order, split by the low feature bits, write the CSR.
+// A bucket of at most kSortCap postings (the usual case) is done in one round: its sorted positions are
+// staged in LDS and written as one contiguous run.  A larger bucket (a very frequent feature) is counted
+// first and then taken in rounds of whole pieces, each round writing behind per-feature cursors.
+__global__ __launch_bounds__(kSplitThreads) void idx_bucket_sort_kernel(IdxDev d, int n_tiles) {
     extern __shared__ __align__(16) uint32_t dyn[];
-    constexpr int kBuf = kSortCap + kSortCap / 32 + 8;
-    uint32_t* bufa = dyn;
-    uint32_t* bufb = dyn + kBuf;
-    int* pref = (int*)(dyn + 2 * kBuf);          // [kSortThreads + 1]
-    uint32_t* pinfo = (uint32_t*)(pref + kSortThreads + 1);   // [kSortThreads]
-    int* wsum = (int*)(pinfo + kSortThreads);     // [16]
-    int* hist = wsum + 16;                        // [256]
-    int* cursor = hist + 256;                     // [256]
-    int* rstart = cursor + 256;                   // [256]
-    int* rend = rstart + 256;                     // [256]
+    uint32_t* bufa = dyn;                          // [kSortCap] gathered entries
+    int32_t* bufb = (int32_t*)(dyn + kSortCap);    // [kSortCap] sorted positions (single-round buckets)
+    int* pref = (int*)(dyn + 2 * kSortCap);        // [kSplitThreads + 1]
+    uint32_t* pinfo = (uint32_t*)(pref + kSplitThreads + 1);   // [kSplitThreads] piece words of the round
+    int* wsum = (int*)(pinfo + kSplitThreads);     // [16]
+    int* hist = wsum + 16;                         // [256] whole-bucket counts (before the first round only)
+    int* rcount = hist;                            //       per-round counts afterwards
+    int* cursor = hist + 256;                      // [256]
+    int* rstart = cursor + 256;                    // [256]
+    int* cnt = rstart + 256;                       // [kSplitWaves << S]
 
-    const int tid = threadIdx.x, b = blockIdx.x, head = blockIdx.y;
+    const int tid = threadIdx.x, lane = tid & 63, b = blockIdx.x, head = blockIdx.y;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int n_b = d.total[(size_t)head * d.NB + b];
     const int out_base = d.bbase[(size_t)head * (d.NB + 1) + b];
-    const int nfl = min(1 << d.S, d.n_feat - (b << d.S));
+    const int nd = 1 << d.S;
+    const int nfl = min(nd, d.n_feat - (b << d.S));
     const uint32_t mask = (1u << d.S) - 1u;
     int32_t* offs = d.offsets + (size_t)head * d.off_stride + ((size_t)b << d.S);
     if (n_b == 0) {
@@ -190,81 +235,103 @@ __global__ __launch_bounds__(kSortThreads) void idx_bucket_sort_kernel(IdxDev d,
     const uint32_t* pc = d.piece + (size_t)head * d.piece_stride + (size_t)b * d.max_tiles;
     const uint32_t* inter = d.inter + (size_t)head * d.inter_stride;
     int32_t* posout = d.positions + (size_t)head * d.pos_stride;
-    const bool multi = n_b > kSortCap;
-    const int lane = tid & 63, wave = tid >> 6;
+    const bool multi = n_b > kSortCap || n_tiles > kSplitThreads;   // more than one round of pieces
 
-    if (tid < 256) hist[tid] = 0;
-    __syncthreads();
     if (multi) {   // count the whole bucket first: the CSR offsets are needed before the first round is written
-        for (int t = wave; t < n_tiles; t += kSortThreads / 64) {
+        if (tid < 256) hist[tid] = 0;
+        __syncthreads();
+        for (int t = wave; t < n_tiles; t += kSplitWaves) {
             uint32_t p = pc[t];
-            int cnt = (int)(p & 0xFFFFu);
+            int c = (int)(p & 0xFFFFu);
             const uint32_t* e = inter + (size_t)t * d.tile_post + (p >> 16);
-            for (int i = lane; i < cnt; i += 64) atomicAdd(&hist[e[i] & mask], 1);
+            for (int i = lane; i < c; i += 64) atomicAdd(&hist[e[i] & mask], 1);
         }
         __syncthreads();
         int tot;
-        int ex = block_excl_scan<kSortThreads>(tid < 256 ? hist[tid] : 0, wsum, tot);
-        if (tid < 256) cursor[tid] = out_base + ex;
+        int ex = block_excl_scan<kSplitThreads>(tid < nd ? hist[tid] : 0, wsum, tot);
+        if (tid < nd) cursor[tid] = out_base + ex;
         if (tid < nfl) offs[tid] = out_base + ex;
         __syncthreads();
     }
 
     for (int tp = 0; tp < n_tiles;) {
-        // take as many whole pieces (in tile order) as fit in one round
+        // take as many whole pieces (in tile order) as fit in one round; thread t looks at piece tp + t
         const int t = tp + tid;
-        uint32_t p = t < n_tiles ? pc[t] : 0u;
-        int cnt = (int)(p & 0xFFFFu);
+        const uint32_t p = t < n_tiles ? pc[t] : 0u;
+        const int c = (int)(p & 0xFFFFu);
         int tot;
-        int ex = block_excl_scan<kSortThreads>(cnt, wsum, tot);
+        const int ex = block_excl_scan<kSplitThreads>(c, wsum, tot);
         pref[tid] = ex;
         pinfo[tid] = p;
-        if (tid == kSortThreads - 1) pref[kSortThreads] = tot;
-        int m = __syncthreads_count(ex + cnt <= kSortCap);
+        if (tid == kSplitThreads - 1) pref[kSplitThreads] = tot;
+        int m = __syncthreads_count(ex + c <= kSortCap);    // prefix property: the first m threads qualify
         m = min(m, n_tiles - tp);
         const int n_r = pref[m];
-        const int E = (n_r + kSortThreads - 1) / kSortThreads;
-
-        for (int i = tid; i < E * kSortThreads; i += kSortThreads) {
-            uint32_t e = 0xFFFFFFFFu;
-            if (i < n_r) {
-                int lo = 0, hi = m;                 // largest j with pref[j] <= i  (pref[m] = n_r > i)
-                while (hi - lo > 1) {
-                    int mid = (lo + hi) >> 1;
-                    if (pref[mid] <= i) lo = mid; else hi = mid;
+        // gather: a half wavefront copies one piece; four pieces per step so that four loads are in flight
+        {
+            const int hw = tid >> 5, l0 = tid & 31;
+            for (int j0 = hw; j0 < m; j0 += 4 * (kSplitThreads / 32)) {
+                const uint32_t* sp[4];
+                int dst[4], cc[4];
+                uint32_t v[4];
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const int j = j0 + q * (kSplitThreads / 32);
+                    const uint32_t pj = j < m ? pinfo[j] : 0u;
+                    cc[q] = (int)(pj & 0xFFFFu);
+                    dst[q] = j < m ? pref[j] : 0;
+                    sp[q] = inter + (size_t)(tp + (j < m ? j : 0)) * d.tile_post + (pj >> 16);
                 }
-                e = inter[(size_t)(tp + lo) * d.tile_post + (pinfo[lo] >> 16) + (i - pref[lo])];
-                if (!multi) atomicAdd(&hist[e & mask], 1);
+#pragma unroll
+                for (int q = 0; q < 4; ++q) v[q] = l0 < cc[q] ? sp[q][l0] : 0u;
+#pragma unroll
+                for (int q = 0; q < 4; ++q)
+                    if (l0 < cc[q]) bufa[dst[q] + l0] = v[q];
+#pragma unroll
+                for (int q = 0; q < 4; ++q)
+                    for (int l = l0 + 32; l < cc[q]; l += 32) bufa[dst[q] + l] = sp[q][l];
             }
-            bufa[padi(i)] = e;
         }
-        if (tid < 256) { rstart[tid] = 0; rend[tid] = 0; }
+        for (int i = tid; i < kSplitWaves * nd; i += kSplitThreads) cnt[i] = 0;
         __syncthreads();
-        if (!multi) {
-            int tot2;
-            int ex2 = block_excl_scan<kSortThreads>(tid < 256 ? hist[tid] : 0, wsum, tot2);
-            if (tid < 256) cursor[tid] = out_base + ex2;
-            if (tid < nfl) offs[tid] = out_base + ex2;
-            __syncthreads();
-        }
-        uint32_t* sorted = bitsplit_sort<kSortThreads>(bufa, bufb, E, 0, d.S, wsum);
-        for (int i = tid; i < n_r; i += kSortThreads) {
-            int fl = (int)(sorted[padi(i)] & mask);
-            int prev = i > 0 ? (int)(sorted[padi(i - 1)] & mask) : -1;
-            if (fl != prev) {
-                rstart[fl] = i;
-                if (prev >= 0) rend[prev] = i;
+
+        int* row = cnt + wave * nd;
+        const int seg = ((n_r + kSplitWaves - 1) / kSplitWaves + 63) & ~63;      // entries per wavefront (<= 512)
+        uint32_t ent[kSplitRounds];
+        unsigned long long peers[kSplitRounds];
+#pragma unroll
+        for (int r = 0; r < kSplitRounds; ++r) {
+            if (r * 64 >= seg) {          // uniform: this round is past the wavefront's share
+                ent[r] = 0u;
+                peers[r] = 0ull;
+                continue;
             }
-            if (i == n_r - 1) rend[fl] = n_r;
+            const int i = wave * seg + r * 64 + lane;
+            const bool valid = i < n_r;
+            ent[r] = valid ? bufa[i] : 0u;
+            peers[r] = same_key_lanes(ent[r] & mask, d.S, valid);
+            split_count(row, ent[r] & mask, peers[r], lane);
         }
         __syncthreads();
-        for (int i = tid; i < n_r; i += kSortThreads) {
-            uint32_t e = sorted[padi(i)];
-            int fl = (int)(e & mask);
-            posout[cursor[fl] + (i - rstart[fl])] = d.pos_log[e >> d.S];
+        split_scan(cnt, nd, rstart, rcount, wsum);
+        if (!multi && tid < nfl) offs[tid] = out_base + rstart[tid];
+#pragma unroll
+        for (int r = 0; r < kSplitRounds; ++r) {
+            if (r * 64 >= seg) continue;
+            const unsigned fl = ent[r] & mask;
+            const int rk = split_rank(row, fl, peers[r], lane);
+            if (peers[r]) {
+                const int32_t pos = d.pos_log[ent[r] >> d.S];
+                if (multi) posout[cursor[fl] + (rk - rstart[fl])] = pos;
+                else bufb[rk] = pos;
+            }
         }
         __syncthreads();
-        if (tid < 256) cursor[tid] += rend[tid] - rstart[tid];
+        if (multi) {
+            if (tid < nd) cursor[tid] += rcount[tid];
+        } else {
+            for (int i = tid; i < n_r; i += kSplitThreads) posout[out_base + i] = bufb[i];
+        }
         tp += m;
         __syncthreads();
     }
@@ -275,9 +342,9 @@ __global__ void idx_fill_positions_kernel(int32_t* dst, int n, int32_t base) {
     if (i < n) dst[i] = base + i;
 }
 
-size_t bucket_sort_lds() {
-    constexpr int kBuf = kSortCap + kSortCap / 32 + 8;
-    return (size_t)2 * kBuf * 4 + (kSortThreads + 1) * 4 + kSortThreads * 4 + 16 * 4 + 4 * 256 * 4;
+size_t bucket_sort_lds(int S) {
+    return (size_t)2 * kSortCap * 4 + (kSplitThreads + 1) * 4 + kSplitThreads * 4 + 16 * 4 + 3 * 256 * 4 +
+           ((size_t)kSplitWaves << S) * 4;
 }
 
 struct Geometry {
@@ -299,7 +366,7 @@ int run_partition(const int32_t* src, int64_t head_stride, int rows, int tile0, 
                   hipStream_t st) {
     if (rows <= 0) return S3_OK;
     int ntiles = (rows + d.ptok - 1) / d.ptok;
-    hipLaunchKernelGGL(idx_partition_kernel, dim3(ntiles, n_heads), dim3(kPartThreads), 0, st, src, head_stride, rows,
+    hipLaunchKernelGGL(idx_partition_kernel, dim3(ntiles, n_heads), dim3(kSplitThreads), 0, st, src, head_stride, rows,
                        tile0, d);
     S3_HIP(hipGetLastError());
     return S3_OK;
@@ -309,12 +376,12 @@ int run_finalize(const IdxDev& d, int n_heads, int n_tiles, hipStream_t st) {
     static bool attr_set = false;
     if (!attr_set) {
         S3_HIP(hipFuncSetAttribute((const void*)idx_bucket_sort_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                   (int)bucket_sort_lds()));
+                                   (int)bucket_sort_lds(8)));
         attr_set = true;
     }
     hipLaunchKernelGGL(idx_totals_kernel, dim3(d.NB, n_heads), dim3(256), 0, st, d, n_tiles);
     hipLaunchKernelGGL(idx_bucket_scan_kernel, dim3(n_heads), dim3(256), 0, st, d);
-    hipLaunchKernelGGL(idx_bucket_sort_kernel, dim3(d.NB, n_heads), dim3(kSortThreads), bucket_sort_lds(), st, d,
+    hipLaunchKernelGGL(idx_bucket_sort_kernel, dim3(d.NB, n_heads), dim3(kSplitThreads), bucket_sort_lds(d.S), st, d,
                        n_tiles);
     S3_HIP(hipGetLastError());
     return S3_OK;
