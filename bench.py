@@ -22,6 +22,10 @@ sys.path.insert(0, ROOT)
 from paper_2601_17702_amd import synth  # noqa: E402
 
 MFMA_PEAK_TFLOPS = {"bf16": 2500.0, "fp32": 157.3}   # MI355X dense matrix peaks
+HBM_PEAK_GBS = 8000.0
+# HBM bytes per launch of the encoder kernel from the rocprofv3 FETCH_SIZE / WRITE_SIZE runs summarised in
+# profiles/bench_c2_llama8b_hbm_traffic.txt (counter runs cannot be made from inside this script)
+MEASURED_TRAFFIC = {"c2_llama8b": 1368194266}
 
 
 def gen_inputs(w, torch, threads=16):
@@ -87,6 +91,8 @@ def main():
     ap.add_argument("--cpu-sample-tokens", type=int, default=0, help="0 = min(L, 32768)")
     ap.add_argument("--cpu-sample-heads", type=int, default=3)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also launch one plain 256 MiB device copy (a kernel of known traffic, for counter runs)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on ONE GPU (no collectives, no sharding); use --gpus 1")
@@ -144,6 +150,12 @@ def main():
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
 
+    if args.calibrate_copy:          # reads 256 MiB, writes 256 MiB: scales the FETCH_SIZE / WRITE_SIZE counters
+        src = torch.zeros(64 << 20, dtype=torch.int32, device="cuda")
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+
     enc_ms = [a.elapsed_time(b) for marks, *_ in timers for a, b, _ in marks]
     app_ms = [b.elapsed_time(d) for marks, *_ in timers for _, b, d in marks]
     fin_ms = [f0.elapsed_time(f1) for _, f0, f1, _, _ in timers]
@@ -154,6 +166,17 @@ def main():
     achieved = flop_per_launch / (enc_avg * 1e-3) / 1e12
     peak = MFMA_PEAK_TFLOPS[w.dtype]
     ms_per_step = dt / args.steps * 1e3
+
+    # algorithmic HBM bytes of the index build and of scoring (every byte that has to move once)
+    idx_bytes = 2.0 * H * w.L * w.k * 4                          # ids in, postings out
+    post_bytes = 0.0
+    qh = qids.cpu().numpy()
+    for h in range(H):
+        off = index.csr(h)[0].cpu().numpy()
+        f = np.unique(qh[h])
+        post_bytes += 4.0 * float((off[f + 1] - off[f]).sum())   # posting lists named by this head's queries
+    score_bytes = post_bytes + 2.0 * H * w.nq * w.k * 4 + 4.0 * w.L
+    idx_ms = float(np.sum(app_ms)) / args.steps + float(np.mean(fin_ms))
     res = {
         "metric": "scanned tokens\u00b7heads/sec (encode+TopK+index) at Llama-8B shape; % MFMA/HBM peak",
         "value": w.token_heads / (ms_per_step * 1e-3),
@@ -168,8 +191,14 @@ def main():
                       "index_finalize": float(np.mean(fin_ms)), "query_encode": float(np.mean(qenc_ms)),
                       "coactivate_score": float(np.mean(score_ms))},
         "roofline": {"kernel": "sae_encode_topk_fast_kernel<0>", "bound": "mfma", "achieved": achieved, "peak": peak,
-                     "unit": "TFLOP/s", "frac": achieved / peak, "traffic": None,
+                     "unit": "TFLOP/s", "frac": achieved / peak, "traffic": MEASURED_TRAFFIC.get(w.name),
                      "launch_ms": enc_avg, "flop_per_launch": flop_per_launch},
+        "stage_rooflines": {
+            "index_build": {"bound": "hbm", "bytes": idx_bytes, "ms": idx_ms, "achieved": idx_bytes / idx_ms / 1e6,
+                            "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": idx_bytes / idx_ms / 1e6 / HBM_PEAK_GBS},
+            "coactivate_score": {"bound": "hbm", "bytes": score_bytes, "ms": float(np.mean(score_ms)),
+                                 "achieved": score_bytes / float(np.mean(score_ms)) / 1e6, "peak": HBM_PEAK_GBS,
+                                 "unit": "GB/s", "frac": score_bytes / float(np.mean(score_ms)) / 1e6 / HBM_PEAK_GBS}},
         "spans_found": int(out[2].item()),
     }
     if not args.no_cpu_baseline:

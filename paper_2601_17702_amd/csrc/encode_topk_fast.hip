@@ -1,27 +1,24 @@
 // Fast path of the fused SAE encoder + Top-k (Sec. 3.3): bf16, d_head = 128, k <= 32,
-// n_feat a multiple of 32.
+// n_feat a multiple of 128.
 //
 // Same method as the generic kernel (features on the MFMA M axis, per-token threshold tau,
 // candidate lists in LDS, exact selection), laid out for two wavefronts per SIMD:
 //
 //   - workgroup = 8 wavefronts = 256 tokens.  W_enc streams through a ring of four 32-feature
 //     stages in LDS.  Each wavefront copies 4 rows of a stage per step straight from global memory
-//     into LDS (no registers in between), three stages ahead of the MFMAs, so a copy has three
-//     whole steps to arrive; one barrier per stage;
+//     into LDS (no registers in between); the copies of a pair of stages are started one pair
+//     (64 features) ahead of their MFMAs; one barrier per pair;
 //   - rows are 256 bytes, unpadded; the sixteen 16-byte pieces of row r are stored at piece index
 //     (c xor (r & 15)), which makes the 16-byte fragment reads of 16 consecutive rows conflict-free;
-//   - b_enc is copied the same way (fp32) and read as the accumulator's initial value, so the
-//     bias costs no vector-ALU instruction;
-//   - wavefronts 0-3 run [MFMA(j), epilogue(j)], wavefronts 4-7 run [epilogue(j-1), MFMA(j)]: the
-//     two wavefronts that share a SIMD are half a stage apart, so one feeds the matrix pipe while
-//     the other runs the compare/append epilogue on the vector ALU;
-//   - the epilogue tests 4 accumulators per uniform branch; each lane owns a fixed list of CAPL
-//     slots, so "list nearly full" is one compare on the lane's write pointer after a group that
-//     appended;
-//   - threshold refreshes are voted per workgroup at the stage barrier, so that all wavefronts
-//     refresh in the same stage instead of stalling each other one after the other; the refresh
-//     loads the lane's candidates into registers once and narrows tau there.  The kernel has ONE
-//     refresh site (voted, emergency and final refresh all pass through it), inlined;
+//   - b_enc is copied the same way (fp32) and read as the accumulator's initial value (the first
+//     MFMA's C operand), so the bias costs no vector-ALU instruction;
+//   - the epilogue of a stage takes the 16 hit masks (accumulator > tau, one scalar mask each) back
+//     to back, then walks them with scalar branches; an accumulator with a survivor somewhere in the
+//     wavefront runs a short append block under that mask.  Each lane owns a fixed list of CAPL slots,
+//     so "list nearly full" is one compare on the lane's write pointer;
+//   - threshold refreshes are voted per workgroup at the pair barrier, so that all wavefronts
+//     refresh at the same point instead of stalling each other one after the other; the refresh
+//     loads the lane's candidates into registers once and narrows tau there;
 //   - the final k candidates of a token are sorted with a 32-lane bitonic network (two tokens per
 //     wavefront step) and written coalesced.
 //
@@ -46,16 +43,15 @@ constexpr int kWaves = 8;
 constexpr int kTokWG = 256;
 constexpr int kFT = 32;          // features per stage (one 32x32 MFMA tile per wavefront)
 constexpr int kRing = 4;         // stages in the LDS ring
-constexpr int kAhead = kRing - 1;
 constexpr int DH = 128;
 constexpr int NS = DH / 16;      // MFMA K steps per stage
 constexpr int RB = DH * 2;       // bytes of one W row
 constexpr int kStageB = kFT * RB;
-constexpr int kBiasB = 256;      // 32 fp32 biases, copied twice (a wavefront-wide copy is 64 lanes wide)
+constexpr int kBiasB = 256;      // the 64 fp32 biases of a pair of stages (one wavefront-wide copy)
 constexpr int CAPL = 40;         // list slots per lane (a token has two lanes)
 constexpr int kGuard = 4;        // appends possible between two fullness checks
 constexpr int kOffBias = kRing * kStageB;
-constexpr int kOffVote = kOffBias + kRing * kBiasB;
+constexpr int kOffVote = kOffBias + (kRing / 2) * kBiasB;
 constexpr int kOffVal = kOffVote + 16;
 constexpr int kOffId = kOffVal + kWaves * 2 * CAPL * 32 * 4;
 constexpr int kLdsBytes = kOffId + kWaves * 2 * CAPL * 32 * 2;
@@ -304,25 +300,27 @@ __global__ __launch_bounds__(kThreads) void sae_encode_topk_fast_kernel(EncParam
     const int k = p.k;
     const int loose = min(k + (k >> 3) + 2, CAPL - kGuard);
     const int nst = p.n_feat / kFT;                                // a multiple of 4
-    const bool late = wv >= kWaves / 2;
 
     // ---- global -> LDS copy of one stage: wavefront w copies rows 4w .. 4w+3 (16 lanes per row); lane l
     // writes piece l of the wavefront's 1 KB, which must hold column piece (l & 15) xor (row & 15) of its row.
-    // Every wavefront also copies the stage's 32 biases (lanes 32-63 repeat them) to the same place: the
-    // copies carry identical bytes, and each wavefront only has to wait for its own.
-    // Stage numbers past the end are clamped: the copy then lands in a ring slot that is not read any more.
+    // Every wavefront also copies the 64 biases of a pair of stages to the same place: the copies carry
+    // identical bytes, and each wavefront only has to wait for its own.
+    // A pair past the end is clamped to the last pair: the copy then lands in ring slots that are not read any more.
     const int crow = wv * 4 + (lane >> 4);
     const char* const wsrc = p.w + (size_t)head * p.n_feat * RB;
     const float* const bsrc = p.b + (size_t)head * p.n_feat;
     const unsigned wlane = (unsigned)(crow * RB + (((lane & 15) ^ (crow & 15)) << 4));
-    const unsigned blane = (unsigned)(n * 4);
-#define S3_LOAD_STAGE(J, BUF)                                                                                \
+    const unsigned blane = (unsigned)(lane * 4);
+    // stages J, J + 1 -> ring slots 2 Q, 2 Q + 1 and bias slot Q
+#define S3_LOAD_PAIR(J, Q)                                                                                   \
     do {                                                                                                     \
-        const int js_ = min((J), nst - 1);                                                                   \
-        __builtin_amdgcn_global_load_lds((glb_cvoid*)(wsrc + (size_t)js_ * kStageB + wlane),                 \
-                                         (lds_void*)(sm + (BUF) * kStageB + wv * 1024), 16, 0, 0);           \
+        const int js_ = min((J), nst - 2);                                                                   \
+        const char* ws_ = wsrc + (size_t)js_ * kStageB + wlane;                                              \
+        __builtin_amdgcn_global_load_lds((glb_cvoid*)ws_, (lds_void*)(sm + (2 * (Q)) * kStageB + wv * 1024), 16, 0, 0); \
+        __builtin_amdgcn_global_load_lds((glb_cvoid*)(ws_ + kStageB),                                        \
+                                         (lds_void*)(sm + (2 * (Q) + 1) * kStageB + wv * 1024), 16, 0, 0);   \
         __builtin_amdgcn_global_load_lds((glb_cvoid*)((const char*)(bsrc + js_ * kFT) + blane),              \
-                                         (lds_void*)(sm + kOffBias + (BUF) * kBiasB), 4, 0, 0);              \
+                                         (lds_void*)(sm + kOffBias + (Q) * kBiasB), 4, 0, 0);                \
     } while (0)
 
     // ---- fragment addresses: lane (row n, half h) reads column piece 2s + h of its row in K step s;
@@ -332,10 +330,12 @@ __global__ __launch_bounds__(kThreads) void sae_encode_topk_fast_kernel(EncParam
     for (int s = 0; s < NS; ++s) xo[s] = sm_a + (unsigned)(n * RB + (((2 * s + half) ^ (n & 15)) << 4));
     const unsigned ba = sm_a + (unsigned)(kOffBias + half * 16);
 
-    f32x16 acc = {};
+    f32x16 acc0 = {}, acc1 = {};     // ping-pong: one is written by the MFMAs while the other one is compared
+    unsigned long long hm[16];       // hit masks of the stage whose epilogue comes next
     // All LDS reads of a step in one statement that also waits for them: 4 x 16 B of biases, 8 x 16 B of W
     // fragments of ring slot BUF, and the vote slot of the previous step.  Declares the step's fragment
     // variables; S3_MFMAS consumes them (the bias vector is the first MFMA's C operand).
+#define S3_BIAS_OFF(BUF) (((BUF) >> 1) * kBiasB + ((BUF) & 1) * 128)
 #define S3_READS(BUF)                                                                                        \
     f32x4 c0_, c1_, c2_, c3_;                                                                                \
     u32x4 f0_, f1_, f2_, f3_, f4_, f5_, f6_, f7_;                                                            \
@@ -358,23 +358,27 @@ __global__ __launch_bounds__(kThreads) void sae_encode_topk_fast_kernel(EncParam
         : "=&v"(c0_), "=&v"(c1_), "=&v"(c2_), "=&v"(c3_), "=&v"(f0_), "=&v"(f1_), "=&v"(f2_), "=&v"(f3_),    \
           "=&v"(f4_), "=&v"(f5_), "=&v"(f6_), "=&v"(f7_), "=&v"(vt_)                                         \
         : "v"(ba), "v"(xo[0]), "v"(xo[1]), "v"(xo[2]), "v"(xo[3]), "v"(xo[4]), "v"(xo[5]), "v"(xo[6]),       \
-          "v"(xo[7]), "v"(vote_a), "n"((BUF) * kBiasB), "n"((BUF) * kBiasB + 32), "n"((BUF) * kBiasB + 64),      \
-          "n"((BUF) * kBiasB + 96), "n"((BUF) * kStageB), "n"((((BUF) + 3) & 3) * 4)                         \
+          "v"(xo[7]), "v"(vote_a), "n"(S3_BIAS_OFF(BUF)), "n"(S3_BIAS_OFF(BUF) + 32), "n"(S3_BIAS_OFF(BUF) + 64), \
+          "n"(S3_BIAS_OFF(BUF) + 96), "n"((BUF) * kStageB), "n"(((((BUF) >> 1) ^ 1) & 1) * 4)                \
         : "memory");                                                                                         \
     S3_T(1)
-#define S3_MFMAS()                                                                                           \
+    // MFMAs of a stage into ACC; the 16 compares of the previous stage's accumulators (PREV) sit between them:
+    // they need no MFMA result of this chain, so they run while the wavefront would otherwise wait for it.
+#define S3_MFMAS(ACC, PREV)                                                                                  \
     {                                                                                                        \
         f32x16 ci_ = __builtin_shufflevector(__builtin_shufflevector(c0_, c1_, 0, 1, 2, 3, 4, 5, 6, 7),      \
                                              __builtin_shufflevector(c2_, c3_, 0, 1, 2, 3, 4, 5, 6, 7),      \
                                              0, 1, 2, 3, 4, 5, 6, 7, 8, 9, 10, 11, 12, 13, 14, 15);          \
-        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, f0_), bfr[0], ci_, 0, 0, 0); \
-        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, f1_), bfr[1], acc, 0, 0, 0); \
-        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, f2_), bfr[2], acc, 0, 0, 0); \
-        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, f3_), bfr[3], acc, 0, 0, 0); \
-        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, f4_), bfr[4], acc, 0, 0, 0); \
-        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, f5_), bfr[5], acc, 0, 0, 0); \
-        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, f6_), bfr[6], acc, 0, 0, 0); \
-        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, f7_), bfr[7], acc, 0, 0, 0); \
+        ACC = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, f0_), bfr[0], ci_, 0, 0, 0); \
+        ACC = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, f1_), bfr[1], ACC, 0, 0, 0); \
+        S3_MASKS8(PREV, 0, "");                                                                              \
+        ACC = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, f2_), bfr[2], ACC, 0, 0, 0); \
+        ACC = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, f3_), bfr[3], ACC, 0, 0, 0); \
+        ACC = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, f4_), bfr[4], ACC, 0, 0, 0); \
+        S3_MASKS8(PREV, 8, "");                                                                              \
+        ACC = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, f5_), bfr[5], ACC, 0, 0, 0); \
+        ACC = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, f6_), bfr[6], ACC, 0, 0, 0); \
+        ACC = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, f7_), bfr[7], ACC, 0, 0, 0); \
     }
 
 #define S3_REFRESH(TARGET)                                                                                   \
@@ -397,8 +401,8 @@ __global__ __launch_bounds__(kThreads) void sae_encode_topk_fast_kernel(EncParam
 #define S3_MFMA_NOPS "s_nop 7\n\ts_nop 4\n\t"
     // Hit masks of accumulators B0 .. B0+7 (one scalar 64-lane mask each), computed back to back so that the
     // branches below wait for no vector compare.
-#define S3_MASKS8(B0, NOPS)                                                                                  \
-    asm(NOPS "v_cmp_gt_f32_e64 %0, %8, %16\n\t"                                                                 \
+#define S3_MASKS8(ACC, B0, NOPS)                                                                                \
+    asm volatile(NOPS "v_cmp_gt_f32_e64 %0, %8, %16\n\t"                                                                 \
         "v_cmp_gt_f32_e64 %1, %9, %16\n\t"                                                                   \
         "v_cmp_gt_f32_e64 %2, %10, %16\n\t"                                                                  \
         "v_cmp_gt_f32_e64 %3, %11, %16\n\t"                                                                  \
@@ -408,12 +412,12 @@ __global__ __launch_bounds__(kThreads) void sae_encode_topk_fast_kernel(EncParam
         "v_cmp_gt_f32_e64 %7, %15, %16"                                                                      \
         : "=s"(hm[(B0) + 0]), "=s"(hm[(B0) + 1]), "=s"(hm[(B0) + 2]), "=s"(hm[(B0) + 3]), "=s"(hm[(B0) + 4]), \
           "=s"(hm[(B0) + 5]), "=s"(hm[(B0) + 6]), "=s"(hm[(B0) + 7])                                         \
-        : "v"(acc[(B0) + 0]), "v"(acc[(B0) + 1]), "v"(acc[(B0) + 2]), "v"(acc[(B0) + 3]), "v"(acc[(B0) + 4]), \
-          "v"(acc[(B0) + 5]), "v"(acc[(B0) + 6]), "v"(acc[(B0) + 7]), "v"(tau))
+        : "v"(ACC[(B0) + 0]), "v"(ACC[(B0) + 1]), "v"(ACC[(B0) + 2]), "v"(ACC[(B0) + 3]), "v"(ACC[(B0) + 4]), \
+          "v"(ACC[(B0) + 5]), "v"(ACC[(B0) + 6]), "v"(ACC[(B0) + 7]), "v"(tau))
     // Accumulator R (feature fb + 8 (R / 4) + R % 4): skipped by a scalar branch when no lane of the wavefront
     // has a survivor; otherwise the lanes of its mask append (value, id), advance their write pointers and
     // record in `full` whether a list got too long.  The workgroup runs with all lanes enabled here.
-#define S3_HIT(R)                                                                                            \
+#define S3_HIT(ACC, R)                                                                                       \
     if (__builtin_expect(hm[R] != 0, 0)) {                                                                   \
         unsigned t_;                                                                                         \
         asm volatile("s_mov_b64 exec, %[m]\n\t"                                                              \
@@ -426,34 +430,32 @@ __global__ __launch_bounds__(kThreads) void sae_encode_topk_fast_kernel(EncParam
                      "s_mov_b64 exec, -1\n\t"                                                                \
                      "s_or_b64 %[full], %[full], vcc"                                                        \
                      : [pv] "+v"(pv), [pi] "+v"(pi), [full] "+s"(full), [t] "=&v"(t_)                        \
-                     : [m] "s"(hm[R]), [a] "v"(acc[R]), [fb] "v"(fb), [c] "n"(8 * ((R) / 4) + (R) % 4),      \
+                     : [m] "s"(hm[R]), [a] "v"(ACC[R]), [fb] "v"(fb), [c] "n"(8 * ((R) / 4) + (R) % 4),      \
                        [lim] "v"(pv_full)                                                                    \
                      : "vcc", "memory");                                                                     \
     }
     // Every lane has >= kGuard free slots at the start of a group of 4 accumulators.  The masks of later
     // groups were taken with the threshold before a refresh: they may name candidates below the new one,
     // which the next refresh drops.
-#define S3_GROUP(G)                                                                                          \
-    S3_HIT(4 * (G) + 0) S3_HIT(4 * (G) + 1) S3_HIT(4 * (G) + 2) S3_HIT(4 * (G) + 3)                          \
+#define S3_GROUP(ACC, G)                                                                                     \
+    S3_HIT(ACC, 4 * (G) + 0) S3_HIT(ACC, 4 * (G) + 1) S3_HIT(ACC, 4 * (G) + 2) S3_HIT(ACC, 4 * (G) + 3)      \
     if (__builtin_expect(full != 0, 0)) {                                                                    \
         S3_REFRESH(loose);                                                                                   \
         full = 0;                                                                                            \
     }
     // Epilogue of stage ST in step JJ: refresh first if the workgroup voted for it in the previous step
     // (the vote slot then holds this step's number), and cast a vote for the next step if a list is long.
-#define S3_EPILOGUE(ST, JJ, SLOT, VT)                                                                          \
+#define S3_VOTED_REFRESH(VT, PP)                                                                             \
+    if (__builtin_expect(__builtin_amdgcn_readfirstlane((int)(VT)) == (PP), 0)) S3_REFRESH(loose);
+#define S3_VOTE_CAST(PP)                                                                                     \
+    if (__builtin_expect(__any(pv > pv_soft), 0)) lds_store_u32(vote_a + ((PP) & 1) * 4, (unsigned)((PP) + 1));
+    // Appends of stage ST, whose accumulators are ACC and whose hit masks are in hm.
+#define S3_HITS(ACC, ST)                                                                                     \
     do {                                                                                                     \
-        if (__builtin_expect(__builtin_amdgcn_readfirstlane((int)(VT)) == (JJ), 0)) S3_REFRESH(loose);       \
-        S3_T(8)                                                                                              \
-        const unsigned fb = (unsigned)((ST) * kFT + half * 4);                                               \
-        unsigned long long hm[16];                                                                           \
-        S3_MASKS8(0, S3_MFMA_NOPS);                                                                          \
-        S3_MASKS8(8, "");                                                                                    \
-        if (ABL & kProfile) asm volatile("" ::"s"(hm[0]), "s"(hm[15]));                                        \
         S3_T(9)                                                                                              \
-        S3_GROUP(0) S3_GROUP(1) S3_GROUP(2) S3_GROUP(3)                                                      \
+        const unsigned fb = (unsigned)((ST) * kFT + half * 4);                                               \
+        S3_GROUP(ACC, 0) S3_GROUP(ACC, 1) S3_GROUP(ACC, 2) S3_GROUP(ACC, 3)                                  \
         S3_T(10)                                                                                             \
-        if (__builtin_expect(__any(pv > pv_soft), 0)) lds_store_u32(vote_a + (SLOT) * 4, (unsigned)((JJ) + 1)); \
     } while (0)
     unsigned long long full = 0;
 #define S3_T(I)                                                                                              \
@@ -466,52 +468,44 @@ __global__ __launch_bounds__(kThreads) void sae_encode_topk_fast_kernel(EncParam
     unsigned rprof[4] = {0, 0, 0, 0};
     unsigned napp = 0;     // candidates this lane appended and later dropped
     unsigned tprev = (ABL & kProfile) ? (unsigned)clock64() : 0u;
-#define S3_BARRIER() stage_barrier<2 * (kAhead - 1)>()
 
     if (tid < 4) lds_store_u32(vote_a + tid * 4, 0xFFFFFFFFu);
-    S3_LOAD_STAGE(0, 0);
-    S3_LOAD_STAGE(1, 1);
-    S3_LOAD_STAGE(2, 2);
+    S3_LOAD_PAIR(0, 0);
     stage_barrier<0>();
 
-    // Step j runs the MFMAs of stage j (ring slot j & 3) and starts the copy of stage j + 3; at its end the
-    // wavefront waits for its copies of stage j + 1 (those of j + 2 and j + 3 stay in flight) and joins the
-    // barrier.  Wavefronts 0-3 handle the epilogue of stage j after the MFMAs of step j, wavefronts 4-7
-    // before the MFMAs of step j + 1.
-    if (!late) {
-#define S3_STEP(B)                                                                                           \
+    // Pair step P (stages 2P, 2P+1 in ring slots 2Q, 2Q+1 with Q = P & 1) starts the copy of the next pair into
+    // the other two slots, runs MFMAs and epilogue of its two stages, waits for its copies and joins the barrier:
+    // one barrier per 64 features, and a copy has a whole pair step to arrive.  A vote cast in pair step P
+    // (slot P & 1 holds P + 1) makes every wavefront refresh at the start of pair step P + 1.
+#define S3_PSTEP(Q)                                                                                          \
     {                                                                                                        \
-        const int jj_ = j + (B);                                                                             \
-        S3_LOAD_STAGE(jj_ + kAhead, ((B) + kAhead) & 3);                                                     \
+        const int pp_ = (j >> 1) + (Q);                                                                      \
+        S3_LOAD_PAIR(2 * pp_ + 2, (Q) ^ 1);                                                                  \
         S3_T(0)                                                                                              \
-        S3_READS(B)                                                                                          \
-        S3_MFMAS()                                                                                           \
-        S3_T(2)                                                                                              \
-        S3_EPILOGUE(jj_, jj_, B, vt_);                                                                       \
+        {                                                                                                    \
+            S3_READS(2 * (Q))                                                                                \
+            S3_MFMAS(acc0, acc1)                                                                             \
+            S3_T(2)                                                                                          \
+            S3_VOTED_REFRESH(vt_, pp_)                                                                       \
+            S3_T(8)                                                                                          \
+            if ((Q) != 0 || j > 0) S3_HITS(acc1, 2 * pp_ - 1);                                               \
+        }                                                                                                    \
+        {                                                                                                    \
+            S3_READS(2 * (Q) + 1)                                                                            \
+            S3_MFMAS(acc1, acc0)                                                                             \
+            S3_T(2)                                                                                          \
+            S3_HITS(acc0, 2 * pp_);                                                                          \
+        }                                                                                                    \
+        S3_VOTE_CAST(pp_)                                                                                    \
         S3_T(3)                                                                                              \
-        S3_BARRIER();                                                                                        \
+        stage_barrier<0>();                                                                                  \
         S3_T(4)                                                                                              \
     }
-        for (int j = 0; j < nst; j += 4) { S3_STEP(0) S3_STEP(1) S3_STEP(2) S3_STEP(3) }
-#undef S3_STEP
-    } else {
-#define S3_STEP(B)                                                                                           \
-    {                                                                                                        \
-        const int jj_ = j + (B);                                                                             \
-        S3_LOAD_STAGE(jj_ + kAhead, ((B) + kAhead) & 3);                                                     \
-        S3_T(0)                                                                                              \
-        S3_READS(B)                                                                                          \
-        if ((B) != 0 || j > 0) S3_EPILOGUE(jj_ - 1, jj_, B, vt_);                                            \
-        S3_T(3)                                                                                              \
-        S3_MFMAS()                                                                                           \
-        S3_T(2)                                                                                              \
-        S3_BARRIER();                                                                                        \
-        S3_T(4)                                                                                              \
-    }
-        for (int j = 0; j < nst; j += 4) { S3_STEP(0) S3_STEP(1) S3_STEP(2) S3_STEP(3) }
-#undef S3_STEP
-        S3_EPILOGUE(nst - 1, nst, 0, lds_load_u32(vote_a + 12));
-    }
+    for (int j = 0; j < nst; j += 4) { S3_PSTEP(0) S3_PSTEP(1) }
+#undef S3_PSTEP
+    S3_MASKS8(acc1, 0, S3_MFMA_NOPS);
+    S3_MASKS8(acc1, 8, "");
+    S3_HITS(acc1, nst - 1);
     stage_barrier<0>();          // no copy may be in flight when the workgroup ends; lists are complete
     S3_REFRESH(k);
     S3_T(5)

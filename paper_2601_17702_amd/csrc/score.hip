@@ -427,7 +427,8 @@ extern "C" int s3_coactivate_score(const s3_index* idx, const int32_t* qids, con
         hipLaunchKernelGGL(sc_qmax_kernel, dim3(blocks(npairs, 256 * 4)), dim3(256), 0, st, a);
         hipLaunchKernelGGL(sc_qacc_kernel, dim3(blocks(npairs, 256)), dim3(256), 0, st, a);
         const size_t nhf = (size_t)a.n_heads * a.n_feat;
-        hipLaunchKernelGGL(sc_qw_kernel, dim3(blocks(nhf, 256)), dim3(256), 0, st, a);
+        // few, long-running blocks: every wavefront ends with one atomic on the same word
+        hipLaunchKernelGGL(sc_qw_kernel, dim3(blocks(nhf, 256 * 16) > 2048 ? 2048 : blocks(nhf, 256 * 16)), dim3(256), 0, st, a);
         if (a.npb) {
             static bool attr_set = false;
             if (!attr_set) {
