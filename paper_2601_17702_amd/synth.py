@@ -67,8 +67,10 @@ WORKLOADS = {
 }
 
 # Zipf recipe constants: b_enc[f] = ZIPF_BETA * (-1.1 * ln rank(f)) + ZIPF_C, fixed so that the
-# most popular features of c3_long are active in >= 1e5 of the 131072 tokens of a head.
-ZIPF_BETA = 0.45
+# most popular features of c3_long are active in >= 1e5 of the 131072 tokens of a head (measured with the
+# oracle on 4096 tokens of head 0: the four most frequent features are in 92 %, 87 %, 86 % and 83 % of the rows,
+# about 1100 of the 16384 features are used at all, the 32 most frequent ones hold half of the postings).
+ZIPF_BETA = 1.0
 ZIPF_C = 9.0
 
 

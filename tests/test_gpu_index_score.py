@@ -228,7 +228,8 @@ def test_window_score_is_exactly_the_sum_of_its_members_and_empty_query():
 
 
 def test_end_to_end_small_streams():
-    """encode -> index -> query encode -> score on shrunken workloads, GPU ids checked against the oracle's."""
+    """encode -> index -> query encode -> score on shrunken workloads.  The oracle runs its own chain end to end
+    (its ids feed its index, its query activations feed its scores); nothing it sees comes from the GPU."""
     import torch
     import paper_2601_17702_amd as s3
     from paper_2601_17702_amd import synth
@@ -241,26 +242,46 @@ def test_end_to_end_small_streams():
         b = np.stack([synth.gen_b_enc(w, h) for h in heads])
         Wg, bg = parity.to_gpu(W, w.dtype), parity.to_gpu(b, "fp32")
         ix = s3.Index(len(heads), n_feat, w.k, L)
-        all_ids = []
+        o_ids, ties = [], 0
         for c in range(w.n_chunks):
             x = np.stack([synth.gen_keys(w, h, c) for h in heads])
             ids, vals = s3.sae_encode_topk(parity.to_gpu(x, w.dtype), Wg, bg, w.k)
             ix.append(ids, base_pos=c * w.T)
             torch.cuda.synchronize()
-            parity.check_encode(ids.cpu().numpy(), vals.cpu().numpy(), x, W, b, w.k, w.dtype)
-            all_ids.append(ids.cpu().numpy())
+            ties += parity.check_encode(ids.cpu().numpy(), vals.cpu().numpy(), x, W, b, w.k, w.dtype)[0]
+            o_ids.append(np.stack([orc.encode_topk(x[i], W[i], b[i], w.k, w.dtype)["ids"] for i in range(len(heads))]))
         ix.finalize()
-        all_ids = np.concatenate(all_ids, axis=1)
+        o_ids = np.concatenate(o_ids, axis=1)
         q = np.stack([synth.gen_queries(w, h) for h in heads])
         qids, qvals = s3.sae_encode_topk(parity.to_gpu(q, w.dtype), Wg, bg, w.k)
         torch.cuda.synchronize()
-        parity.check_encode(qids.cpu().numpy(), qvals.cpu().numpy(), q, W, b, w.k, w.dtype)
-        # index: bit-exact given the same ids; scores: oracle fed with the GPU's ids/vals
+        ties += parity.check_encode(qids.cpu().numpy(), qvals.cpu().numpy(), q, W, b, w.k, w.dtype)[0]
+        oq = [orc.encode_topk(q[i], W[i], b[i], w.k, w.dtype) for i in range(len(heads))]
+        oq_ids, oq_vals = np.stack([o["ids"] for o in oq]), np.stack([o["vals"] for o in oq]).astype(np.float32)
+        assert ties == 0, "pick another seed/size: a near-tie row makes the two chains select different features"
         for i in range(len(heads)):
-            _, (off_o, pos_o) = oracle_csr(all_ids[i], np.arange(L, dtype=np.int32), n_feat)
+            _, (off_o, pos_o) = oracle_csr(o_ids[i], np.arange(L, dtype=np.int32), n_feat)
             assert_csr_equal(ix, i, off_o, pos_o)
         qi, qv = qids.cpu().numpy(), qvals.cpu().numpy()
         for max_freq in (0, 50):
-            S, Wd, st_o, sc_o = oracle_score(all_ids, qi, qv, n_feat, L, w.span_len, w.top_b, max_freq, True)
+            S, Wd, st_o, sc_o = oracle_score(o_ids, oq_ids, oq_vals, n_feat, L, w.span_len, w.top_b, max_freq, True)
             out = run_gpu_score(ix, qi, qv, L, w.span_len, w.top_b, max_freq, True)
             check_score(out, S, Wd, st_o, sc_o, w.span_len, True)
+
+
+def test_scatter_position_blocks_long_lists_sorted_and_unsorted():
+    """More than one LDS block of positions, posting lists long enough to be narrowed by binary search, and the
+    same index fed with explicit positions in a scrambled order (lists unsorted: every posting is filtered)."""
+    rng = np.random.default_rng(1234)
+    H, T, k, n_feat, nq = 2, 40000, 8, 512, 12
+    ids = np.stack([rand_ids(rng, T, k, n_feat, hot=5) for _ in range(H)])
+    qids = np.stack([rand_ids(rng, nq, k, n_feat) for _ in range(H)])
+    qids[:, 0, 0] = 5                                          # the hot feature (a list of T postings) is queried
+    qvals = rng.random((H, nq, k)).astype(np.float32)
+    ix = gpu_index(ids, n_feat, chunks=[4096] * 10)
+    S, W, st_o, sc_o = oracle_score(ids, qids, qvals, n_feat, T, 64, 8, 0, True)
+    check_score(run_gpu_score(ix, qids, qvals, T, 64, 8, 0, True), S, W, st_o, sc_o, 64, True)
+    perm = rng.permutation(T).astype(np.int32)
+    ix2 = gpu_index(ids, n_feat, positions=perm, chunks=[4096] * 10)
+    S2, W2, st2, sc2 = oracle_score(ids, qids, qvals, n_feat, T, 64, 8, 0, True, positions=perm)
+    check_score(run_gpu_score(ix2, qids, qvals, T, 64, 8, 0, True), S2, W2, st2, sc2, 64, True)
