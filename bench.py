@@ -109,16 +109,19 @@ def main():
     qvals = torch.empty((H, w.nq, w.k), dtype=torch.float32, device="cuda")
     index = s3.Index(H, w.n_feat, w.k, w.L)
     ws = torch.empty(index.score_workspace(w.L), dtype=torch.uint8, device="cuda")
+    enc_ws = torch.empty(max(s3.sae_encode_topk_stream_workspace(H, w.T), 1), dtype=torch.uint8, device="cuda")
+    tau_hint = s3.new_tau_hint(H)
     ev = lambda: torch.cuda.Event(enable_timing=True)  # noqa: E731
 
     def step(timers=None):
         index.reset()
+        tau_hint.fill_(float("-inf"))            # a new stream: no threshold is carried into its first chunk
         marks = []
         for c in range(w.n_chunks):
             if timers is not None:
                 a, b, d = ev(), ev(), ev()
                 a.record()
-            s3.sae_encode_topk(K[c], W, B, w.k, ids, vals)
+            s3.sae_encode_topk_stream(K[c], W, B, w.k, tau_hint, enc_ws, ids, vals)
             if timers is not None:
                 b.record()
             index.append(ids, base_pos=c * w.T)

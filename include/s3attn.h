@@ -64,6 +64,27 @@ int s3_sae_encode_topk(const void* x, int dtype, int T, int d_head, const void* 
                        const float* b_enc, int n_feat, int k, int n_heads, int32_t* ids,
                        float* vals, void* stream);
 
+/* The same operation for the chunks of one stream (Alg. 1, Phase 1: the prefill walks the context
+ * chunk by chunk with the same encoder), with a selection threshold carried from chunk to chunk.
+ * Results are identical to s3_sae_encode_topk for ANY contents of tau_hint: the carried values
+ * only set where the exact Top-K selection (Sec. 3.3) of a token starts; a token whose start was
+ * too high (fewer than k pre-activations above it) is selected again from scratch inside the same
+ * call.  The k-th largest pre-activation of a token scales with |x_t|, so the smallest
+ * tau_t / |x_t| (and the smallest tau_t) of one chunk are good starts for the next one.
+ *
+ *   tau_hint [n_heads][2] fp32, device, read and overwritten: lower bounds of tau_t / |x_t| and
+ *            of tau_t over the tokens of the previous call.  Fill with -INFINITY before the
+ *            first chunk of a stream (no bound: same work as s3_sae_encode_topk).
+ *   ws       s3_sae_encode_topk_stream_workspace(n_heads, T) bytes, 256-byte aligned, device;
+ *            scratch, contents meaningless between calls.
+ * Shapes the threshold-carrying kernel is not built for (anything but bf16, d_head 128, k <= 32,
+ * n_feat % 128 == 0) run exactly as s3_sae_encode_topk and leave tau_hint untouched.
+ * Errors as s3_sae_encode_topk; S3_ECAPACITY if ws_bytes is too small. */
+size_t s3_sae_encode_topk_stream_workspace(int n_heads, int T);
+int s3_sae_encode_topk_stream(const void* x, int dtype, int T, int d_head, const void* w_enc,
+                              const float* b_enc, int n_feat, int k, int n_heads, int32_t* ids,
+                              float* vals, float* tau_hint, void* ws, size_t ws_bytes, void* stream);
+
 /* ------------------------------------------------------------------------------------------
  * Sec. 3.4, inverted semantic index: for all f in F_t, I[f] <- I[f] U {t}, held on the GPU in
  * the contiguous form the paper recommends (Sec. 3.4 "CPU Index Size"): per head a CSR with

@@ -34,6 +34,9 @@ def lib():
         vp, i32, i64, ci, sz = C.c_void_p, C.c_int32, C.c_int64, C.c_int, C.c_size_t
         L.s3_last_error.restype = C.c_char_p
         L.s3_sae_encode_topk.argtypes = [vp, ci, ci, ci, vp, vp, ci, ci, ci, vp, vp, vp]
+        L.s3_sae_encode_topk_stream.argtypes = [vp, ci, ci, ci, vp, vp, ci, ci, ci, vp, vp, vp, vp, sz, vp]
+        L.s3_sae_encode_topk_stream_workspace.argtypes = [ci, ci]
+        L.s3_sae_encode_topk_stream_workspace.restype = sz
         L.s3_index_create.argtypes = [ci, ci, ci, i64, C.POINTER(vp)]
         L.s3_index_destroy.argtypes = [vp]
         L.s3_index_destroy.restype = None
@@ -52,7 +55,7 @@ def lib():
         L.s3_coactivate_score_workspace.argtypes = [vp, i64]
         L.s3_coactivate_score_workspace.restype = sz
         L.s3_coactivate_score.argtypes = [vp, vp, vp, ci, i64, ci, ci, i32, ci, vp, vp, vp, vp, vp, sz, vp]
-        for name in ("s3_sae_encode_topk", "s3_index_create", "s3_index_append", "s3_index_finalize",
+        for name in ("s3_sae_encode_topk", "s3_sae_encode_topk_stream", "s3_index_create", "s3_index_append", "s3_index_finalize",
                      "s3_index_csr", "s3_index_build", "s3_coactivate_score"):
             getattr(L, name).restype = ci
         _lib = L
@@ -100,6 +103,43 @@ def sae_encode_topk(x, w_enc, b_enc, k: int, ids=None, vals=None):
     assert ids.numel() == n_heads * T * k and vals.numel() == n_heads * T * k
     _check(lib().s3_sae_encode_topk(_ptr(x), _dtype_code(x), T, d, _ptr(w_enc), _ptr(b_enc), n_feat, k, n_heads,
                                     _ptr(ids), _ptr(vals), _stream()))
+    return ids, vals
+
+
+def new_tau_hint(n_heads: int, device="cuda"):
+    """Carried thresholds of a stream before its first chunk: [n_heads, 2] fp32 filled with -inf."""
+    import torch
+    return torch.full((n_heads, 2), float("-inf"), dtype=torch.float32, device=device)
+
+
+def sae_encode_topk_stream_workspace(n_heads: int, T: int) -> int:
+    return int(lib().s3_sae_encode_topk_stream_workspace(n_heads, T))
+
+
+def sae_encode_topk_stream(x, w_enc, b_enc, k: int, tau_hint, ws=None, ids=None, vals=None):
+    """sae_encode_topk for the chunks of one stream: tau_hint [n_heads, 2] fp32 (new_tau_hint) is read and updated;
+    the results are the same as sae_encode_topk's whatever it holds."""
+    import torch
+    assert x.is_cuda and x.is_contiguous() and w_enc.is_contiguous() and b_enc.is_contiguous()
+    assert x.dim() == 3 and w_enc.dim() == 3 and b_enc.dim() == 2
+    n_heads, T, d = x.shape
+    n_feat = w_enc.shape[1]
+    assert w_enc.shape == (n_heads, n_feat, d) and b_enc.shape == (n_heads, n_feat)
+    assert w_enc.dtype == x.dtype and b_enc.dtype == torch.float32
+    assert tau_hint.is_cuda and tau_hint.is_contiguous() and tau_hint.dtype == torch.float32
+    assert tau_hint.numel() == 2 * n_heads
+    need = sae_encode_topk_stream_workspace(n_heads, T)
+    if ws is None:
+        ws = torch.empty(max(need, 1), dtype=torch.uint8, device=x.device)
+    assert ws.numel() >= need
+    if ids is None:
+        ids = torch.empty((n_heads, T, k), dtype=torch.int32, device=x.device)
+    if vals is None:
+        vals = torch.empty((n_heads, T, k), dtype=torch.float32, device=x.device)
+    assert ids.is_contiguous() and vals.is_contiguous() and ids.dtype == torch.int32 and vals.dtype == torch.float32
+    assert ids.numel() == n_heads * T * k and vals.numel() == n_heads * T * k
+    _check(lib().s3_sae_encode_topk_stream(_ptr(x), _dtype_code(x), T, d, _ptr(w_enc), _ptr(b_enc), n_feat, k, n_heads,
+                                           _ptr(ids), _ptr(vals), _ptr(tau_hint), _ptr(ws), ws.numel(), _stream()))
     return ids, vals
 
 

@@ -353,18 +353,24 @@ int env_int(const char* name, int dflt) {
     return s && *s ? atoi(s) : dflt;
 }
 
-extern "C" int s3_sae_encode_topk(const void* x, int dtype, int T, int d_head, const void* w_enc,
-                                  const float* b_enc, int n_feat, int k, int n_heads, int32_t* ids,
-                                  float* vals, void* stream) {
-    if (!x || !w_enc || !b_enc || !ids || !vals) return s3_fail(S3_EINVAL, "s3_sae_encode_topk: null pointer");
-    if (dtype != S3_BF16 && dtype != S3_FP32) return s3_fail(S3_EINVAL, "s3_sae_encode_topk: dtype must be S3_BF16 or S3_FP32");
+static int encode_impl(const char* who, const void* x, int dtype, int T, int d_head, const void* w_enc, const float* b_enc,
+                       int n_feat, int k, int n_heads, int32_t* ids, float* vals, float* tau_hint, void* ws,
+                       size_t ws_bytes, void* stream) {
+    if (!x || !w_enc || !b_enc || !ids || !vals) return s3_fail(S3_EINVAL, "%s: null pointer", who);
+    if (dtype != S3_BF16 && dtype != S3_FP32) return s3_fail(S3_EINVAL, "%s: dtype must be S3_BF16 or S3_FP32", who);
     if (d_head != 64 && d_head != 128 && d_head != 256)
-        return s3_fail(S3_EINVAL, "s3_sae_encode_topk: d_head %d not in {64, 128, 256}", d_head);
-    if (T < 0 || n_heads < 1) return s3_fail(S3_EINVAL, "s3_sae_encode_topk: T %d / n_heads %d out of range", T, n_heads);
-    if (n_feat < 1 || n_feat > S3_MAX_FEAT) return s3_fail(S3_EINVAL, "s3_sae_encode_topk: n_feat %d not in [1, %d]", n_feat, S3_MAX_FEAT);
-    if (k < 1 || k > n_feat || k > S3_MAX_K) return s3_fail(S3_EINVAL, "s3_sae_encode_topk: k %d not in [1, min(n_feat, %d)]", k, S3_MAX_K);
-    if (((uintptr_t)x | (uintptr_t)w_enc) & 15) return s3_fail(S3_EINVAL, "s3_sae_encode_topk: x and w_enc must be 16-byte aligned");
-    if ((int64_t)n_heads * ((T + kTokWG - 1) / kTokWG) > 0x7FFFFFFFLL) return s3_fail(S3_EINVAL, "s3_sae_encode_topk: grid too large");
+        return s3_fail(S3_EINVAL, "%s: d_head %d not in {64, 128, 256}", who, d_head);
+    if (T < 0 || n_heads < 1) return s3_fail(S3_EINVAL, "%s: T %d / n_heads %d out of range", who, T, n_heads);
+    if (n_feat < 1 || n_feat > S3_MAX_FEAT) return s3_fail(S3_EINVAL, "%s: n_feat %d not in [1, %d]", who, n_feat, S3_MAX_FEAT);
+    if (k < 1 || k > n_feat || k > S3_MAX_K) return s3_fail(S3_EINVAL, "%s: k %d not in [1, min(n_feat, %d)]", who, k, S3_MAX_K);
+    if (((uintptr_t)x | (uintptr_t)w_enc) & 15) return s3_fail(S3_EINVAL, "%s: x and w_enc must be 16-byte aligned", who);
+    if ((int64_t)n_heads * ((T + kTokWG - 1) / kTokWG) > 0x7FFFFFFFLL) return s3_fail(S3_EINVAL, "%s: grid too large", who);
+    if (tau_hint) {
+        if (!ws) return s3_fail(S3_EINVAL, "%s: null workspace", who);
+        if ((uintptr_t)ws & 255) return s3_fail(S3_EINVAL, "%s: workspace must be 256-byte aligned", who);
+        const size_t need = s3_encode_fast_stream_workspace(n_heads, T);
+        if (ws_bytes < need) return s3_fail(S3_ECAPACITY, "%s: workspace %zu < %zu bytes", who, ws_bytes, need);
+    }
     if (T == 0) return S3_OK;
 
     EncParams p;
@@ -372,16 +378,37 @@ extern "C" int s3_sae_encode_topk(const void* x, int dtype, int T, int d_head, c
     p.T = T; p.n_feat = n_feat; p.k = k; p.n_heads = n_heads;
     p.ablate = env_int("S3_ENC_ABLATE", 0);
     hipStream_t st = (hipStream_t)stream;
-    if (s3_encode_fast_ok(dtype, d_head, n_feat, k) && env_int("S3_ENC_GENERIC", 0) == 0) return s3_encode_fast_launch(p, st);
+    if (s3_encode_fast_ok(dtype, d_head, n_feat, k) && env_int("S3_ENC_GENERIC", 0) == 0)
+        return tau_hint ? s3_encode_fast_stream(p, tau_hint, ws, st) : s3_encode_fast_launch(p, st);
     p.tiles_per_head = (T + kTokWG - 1) / kTokWG;
     // list capacity per token: k survivors + headroom for one tile + room for new candidates between refreshes
     int capt = k + kHeadroom + (k <= 32 ? 16 : 32);
     capt = env_int("S3_ENC_CAPT", capt);
-    if (capt < k + kHeadroom + 4 || capt > 512) return s3_fail(S3_EINVAL, "s3_sae_encode_topk: bad S3_ENC_CAPT %d", capt);
+    if (capt < k + kHeadroom + 4 || capt > 512) return s3_fail(S3_EINVAL, "%s: bad S3_ENC_CAPT %d", who, capt);
     p.capt = capt;
 #define S3_CASE(DT, DH) if (dtype == DT && d_head == DH) return launch<DT, DH>(p, n_heads, st);
     S3_CASE(S3_BF16, 64) S3_CASE(S3_BF16, 128) S3_CASE(S3_BF16, 256)
     S3_CASE(S3_FP32, 64) S3_CASE(S3_FP32, 128) S3_CASE(S3_FP32, 256)
 #undef S3_CASE
-    return s3_fail(S3_EINVAL, "s3_sae_encode_topk: unsupported configuration");
+    return s3_fail(S3_EINVAL, "%s: unsupported configuration", who);
+}
+
+extern "C" int s3_sae_encode_topk(const void* x, int dtype, int T, int d_head, const void* w_enc,
+                                  const float* b_enc, int n_feat, int k, int n_heads, int32_t* ids,
+                                  float* vals, void* stream) {
+    return encode_impl("s3_sae_encode_topk", x, dtype, T, d_head, w_enc, b_enc, n_feat, k, n_heads, ids, vals, nullptr,
+                       nullptr, 0, stream);
+}
+
+extern "C" size_t s3_sae_encode_topk_stream_workspace(int n_heads, int T) {
+    if (n_heads < 1 || T < 0) return 0;
+    return s3_encode_fast_stream_workspace(n_heads, T);
+}
+
+extern "C" int s3_sae_encode_topk_stream(const void* x, int dtype, int T, int d_head, const void* w_enc,
+                                         const float* b_enc, int n_feat, int k, int n_heads, int32_t* ids,
+                                         float* vals, float* tau_hint, void* ws, size_t ws_bytes, void* stream) {
+    if (!tau_hint) return s3_fail(S3_EINVAL, "s3_sae_encode_topk_stream: null tau_hint");
+    return encode_impl("s3_sae_encode_topk_stream", x, dtype, T, d_head, w_enc, b_enc, n_feat, k, n_heads, ids, vals,
+                       tau_hint, ws, ws_bytes, stream);
 }

@@ -50,6 +50,7 @@ constexpr int kStageB = kFT * RB;
 constexpr int kBiasB = 256;      // the 64 fp32 biases of a pair of stages (one wavefront-wide copy)
 constexpr int CAPL = 40;         // list slots per lane (a token has two lanes)
 constexpr int kGuard = 4;        // appends possible between two fullness checks
+constexpr float kHintMargin = 0.02f;   // streamed calls start 2 % below the carried bound
 constexpr int kOffBias = kRing * kStageB;
 constexpr int kOffVote = kOffBias + (kRing / 2) * kBiasB;
 constexpr int kOffVal = kOffVote + 16;
@@ -101,6 +102,10 @@ __device__ __forceinline__ float key_value(unsigned k) {
 __device__ __forceinline__ int pair_sum(int x) {
     auto r = __builtin_amdgcn_permlane32_swap((unsigned)x, (unsigned)x, false, false);
     return (int)(r[0] + r[1]);
+}
+__device__ __forceinline__ float pair_fsum(float x) {
+    auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    return __uint_as_float(r[0]) + __uint_as_float(r[1]);
 }
 __device__ __forceinline__ float pair_max(float x) {
     auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
@@ -276,8 +281,14 @@ __global__ __launch_bounds__(kThreads) void sae_encode_topk_fast_kernel(EncParam
     const int n = lane & 31, half = lane >> 5;
     int head, tt;
     s3_block_to_tile(blockIdx.x, p.n_heads, p.tiles_per_head, head, tt);
-    const int tok = tt * kTokWG + wv * 32 + n;
-    const bool tok_ok = tok < p.T;
+    int tok = tt * kTokWG + wv * 32 + n;
+    bool tok_ok = tok < p.T;
+    if (p.mode == 2) {      // redo pass: this workgroup's tokens come from the head's list (uniform early exit)
+        const int rc = p.redo_cnt[head];
+        if (tt * kTokWG >= rc) return;
+        tok_ok = tok < rc;
+        tok = tok_ok ? p.redo_list[(size_t)head * p.T + tok] : 0;
+    }
 
     bf16x8 bfr[NS];
     {
@@ -297,6 +308,30 @@ __global__ __launch_bounds__(kThreads) void sae_encode_topk_fast_kernel(EncParam
     const unsigned pv_full = pv0a + (CAPL - kGuard) * 128;         // above this a group of 4 may not fit
     const unsigned pv_soft = pv0a + (p.soft > 0 ? p.soft : CAPL) * 128;                  // above this the lane asks for a voted refresh
     float tau = (ABL & kNoHits) ? INFINITY : -INFINITY;
+    // |x| of the lane's token: the k-th largest pre-activation of a token scales with it, which makes the
+    // previous chunk's smallest tau / |x| a useful starting threshold for this chunk's tokens
+    float xnorm;
+    {
+        float ss = 0.f;
+#pragma unroll
+        for (int s = 0; s < NS; ++s) {
+            const u32x4 u = __builtin_bit_cast(u32x4, bfr[s]);
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const float lo = __uint_as_float(u[j] << 16), hi = __uint_as_float(u[j] & 0xFFFF0000u);
+                ss += lo * lo + hi * hi;
+            }
+        }
+        xnorm = sqrtf(pair_fsum(ss));
+    }
+    if (p.mode == 1 && !(ABL & kNoHits)) {
+        // carried bounds, lowered by a margin (a bound that is still too high only costs a redo of that token)
+        const float hr = p.hint_in[2 * head], ha = p.hint_in[2 * head + 1];
+        const float tr = hr > -INFINITY ? hr * xnorm : -INFINITY;
+        const float t0 = fmaxf(tr, ha);
+        tau = t0 > -INFINITY ? t0 - p.margin * fabsf(t0) : -INFINITY;
+    }
+    if (!tok_ok) tau = INFINITY;      // lanes without a token (ragged last tile, short redo list) collect nothing
     const int k = p.k;
     const int loose = min(k + (k >> 3) + 2, CAPL - kGuard);
     const int nst = p.n_feat / kFT;                                // a multiple of 4
@@ -519,17 +554,37 @@ __global__ __launch_bounds__(kThreads) void sae_encode_topk_fast_kernel(EncParam
         if (wv == 0) for (int i = 0; i < 4; ++i) s3_prof[24 + i] = rprof[i];
     }
 
+    const int cnt = (int)(pv - pv0a) >> 7;
+    // A token that started from a carried bound and ends with fewer than k candidates is queued for the redo
+    // pass (its rows are written there).  Every other token reports its final threshold: the minima over the
+    // call (of tau / |x| and of tau) are the bounds carried to the next chunk.
+    const bool failed = tok_ok && pair_sum(cnt) < k;
+    if (p.mode != 0) {
+        if (failed && half == 0) p.redo_list[(size_t)head * p.T + atomicAdd(&p.redo_cnt[head], 1)] = tok;
+        float r = tok_ok && !failed && xnorm > 0.f ? tau / xnorm : INFINITY;
+        float a = tok_ok && !failed ? tau : INFINITY;
+#pragma unroll
+        for (int d = 16; d > 0; d >>= 1) {
+            r = fminf(r, __shfl_xor(r, d));
+            a = fminf(a, __shfl_xor(a, d));
+        }
+        if (lane == 0) {
+            if (r < INFINITY) atomicMin(&p.hint_out[2 * head], ordered_key(r));
+            if (a < INFINITY) atomicMin(&p.hint_out[2 * head + 1], ordered_key(a));
+        }
+    }
+
     // bitonic sort of each token's k candidates: lanes 0-31 sort token 2 it, lanes 32-63 token 2 it + 1;
     // order (z descending, id ascending); lane e ends up with rank e.
-    const int cnt = (int)(pv - pv0a) >> 7;
     const lds_f32* const wcv = (lds_f32*)(sm + kOffVal) + wv * 2 * CAPL * 32;     // this wavefront's lists
     const lds_u16* const wci = (lds_u16*)(sm + kOffId) + wv * 2 * CAPL * 32;
     int32_t* ids_h = p.ids + (size_t)head * p.T * k;
     float* vals_h = p.vals + (size_t)head * p.T * k;
-    const int tok0 = tt * kTokWG + wv * 32;
+    const int wtok = tok_ok && !failed ? tok : -1;          // row this lane's token is written to
     for (int it = 0; it < 16; ++it) {
-        if (tok0 + 2 * it >= p.T) break;
         const int t = 2 * it + half;
+        const int trow = __shfl(wtok, t);
+        if (!__any(trow >= 0)) continue;
         const int clo = __shfl(cnt, t), chi = __shfl(cnt, t + 32);
         const int e = n;
         const bool valid = e < clo + chi;
@@ -550,12 +605,23 @@ __global__ __launch_bounds__(kThreads) void sae_encode_topk_fast_kernel(EncParam
                 id = keep ? id : pid;
             }
         }
-        if (e < k && tok0 + t < p.T) {
-            size_t o = (size_t)(tok0 + t) * k + e;
+        if (e < k && trow >= 0) {
+            size_t o = (size_t)trow * k + e;
             ids_h[o] = (int32_t)id;
             vals_h[o] = fmaxf(key_value(kv), 0.f);
         }
     }
+}
+
+// Streamed calls: counters and this call's minima start empty; afterwards the minima become the carried bounds.
+__global__ void enc_stream_prep_kernel(int32_t* redo_cnt, unsigned* hint_out, int n_heads) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n_heads) redo_cnt[i] = 0;
+    if (i < 2 * n_heads) hint_out[i] = 0xFFFFFFFFu;
+}
+__global__ void enc_stream_post_kernel(const unsigned* hint_out, float* hint, int n_heads) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < 2 * n_heads) hint[i] = hint_out[i] == 0xFFFFFFFFu ? -INFINITY : key_value(hint_out[i]);
 }
 
 template <int ABL>
@@ -579,7 +645,41 @@ bool s3_encode_fast_ok(int dtype, int d_head, int n_feat, int k) {
     return dtype == S3_BF16 && d_head == DH && k <= 32 && n_feat % (4 * kFT) == 0;
 }
 
+static int fast_dispatch(EncParams p, hipStream_t st);
+
 int s3_encode_fast_launch(EncParams p, hipStream_t st) {
+    p.mode = 0;
+    p.hint_in = nullptr; p.hint_out = nullptr; p.redo_list = nullptr; p.redo_cnt = nullptr;
+    return fast_dispatch(p, st);
+}
+
+size_t s3_encode_fast_stream_workspace(int n_heads, int T) {
+    return s3_align((size_t)n_heads * 4) + s3_align((size_t)n_heads * 8) + s3_align((size_t)n_heads * T * 4);
+}
+
+// Main pass from the carried bounds, redo pass (from -inf) for the tokens whose bound was too high, then this
+// call's minima become the bounds for the next call.  All on `st`; nothing is read back.
+int s3_encode_fast_stream(EncParams p, float* hint, void* ws, hipStream_t st) {
+    char* base = (char*)ws;
+    p.redo_cnt = (int32_t*)base;
+    p.hint_out = (unsigned*)(base + s3_align((size_t)p.n_heads * 4));
+    p.redo_list = (int32_t*)(base + s3_align((size_t)p.n_heads * 4) + s3_align((size_t)p.n_heads * 8));
+    p.hint_in = hint;
+    const int nb = (2 * p.n_heads + 255) / 256;
+    hipLaunchKernelGGL(enc_stream_prep_kernel, dim3(nb), dim3(256), 0, st, p.redo_cnt, p.hint_out, p.n_heads);
+    p.margin = (float)env_int("S3_ENC_MARGIN", (int)(kHintMargin * 1000.f + 0.5f)) * 1e-3f;   // per mille, tuning
+    p.mode = 1;
+    int rc = fast_dispatch(p, st);
+    if (rc) return rc;
+    p.mode = 2;
+    rc = fast_dispatch(p, st);
+    if (rc) return rc;
+    hipLaunchKernelGGL(enc_stream_post_kernel, dim3(nb), dim3(256), 0, st, p.hint_out, hint, p.n_heads);
+    S3_HIP(hipGetLastError());
+    return S3_OK;
+}
+
+static int fast_dispatch(EncParams p, hipStream_t st) {
     static_assert(CAPL >= 32 + kGuard, "a lane must be able to hold k survivors and one more group");
     static_assert(kLdsBytes <= 160 * 1024, "LDS budget of one CU");
     p.soft = env_int("S3_ENC_SOFT", 33);                           // list length that asks for a voted refresh (0 = off)

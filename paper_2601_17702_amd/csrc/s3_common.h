@@ -36,11 +36,20 @@ struct EncParams {
     float* vals;
     int T, n_feat, k, n_heads, capt, tiles_per_head, ablate;
     int soft;      // fast path: list length per lane that asks for a workgroup-wide refresh (0: off)
+    // streamed calls (threshold carried from the previous chunk), fast path only
+    float margin;              // relative margin below the carried bound
+    int mode;                  // 0 plain, 1 start from the carried bound, 2 redo the tokens listed in redo_list
+    const float* hint_in;      // [n_heads][2]: lower bounds of tau / |x| and of tau seen in the previous call
+    unsigned* hint_out;        // [n_heads][2]: ordered keys of this call's minima (atomicMin)
+    int32_t* redo_list;        // [n_heads][T] tokens whose carried bound was too high
+    int32_t* redo_cnt;         // [n_heads]
 };
 
 int env_int(const char* name, int dflt);
 bool s3_encode_fast_ok(int dtype, int d_head, int n_feat, int k);   // shapes the fast kernel is built for
 int s3_encode_fast_launch(EncParams p, hipStream_t st);
+size_t s3_encode_fast_stream_workspace(int n_heads, int T);
+int s3_encode_fast_stream(EncParams p, float* hint, void* ws, hipStream_t st);   // hint [n_heads][2] device, in/out
 
 // Workgroup -> (head, token tile).  Workgroups are dealt round-robin to the 8 XCDs (each with its own
 // L2), so consecutive tiles of one head are placed on the SAME XCD: they stream the same W_enc rows at

@@ -107,3 +107,48 @@ def test_bitwise_deterministic():
     a = run(x, W, b, w.k, w.dtype)
     c = run(x, W, b, w.k, w.dtype)
     assert np.array_equal(a[0], c[0]) and np.array_equal(a[1], c[1])
+
+
+def test_streamed_calls_equal_plain_calls_whatever_the_carried_threshold_holds():
+    """Chunks of one stream through s3_sae_encode_topk_stream: bit-identical to s3_sae_encode_topk with the
+    thresholds carried from chunk to chunk, with no carried threshold, and with one that is absurdly high
+    (every token is then selected again from scratch inside the call)."""
+    import torch
+    import paper_2601_17702_amd as s3
+    from oracle import s3_oracle as orc
+    w = synth.shrink(synth.WORKLOADS["c2_llama8b"], L=3 * 600, T=600, n_feat=2048)
+    heads = [0, 3, 9]
+    W, b = np.stack([synth.gen_w_enc(w, h) for h in heads]), np.stack([synth.gen_b_enc(w, h) for h in heads])
+    Wg, bg = parity.to_gpu(W, w.dtype), parity.to_gpu(b, "fp32")
+    hint = s3.new_tau_hint(len(heads))
+    seen = []
+    for c in range(w.n_chunks):
+        x = np.stack([synth.gen_keys(w, h, c) for h in heads])
+        xg = parity.to_gpu(x, w.dtype)
+        ids0, vals0 = s3.sae_encode_topk(xg, Wg, bg, w.k)
+        before = hint.clone()
+        ids1, vals1 = s3.sae_encode_topk_stream(xg, Wg, bg, w.k, hint)
+        torch.cuda.synchronize()
+        assert torch.equal(ids0, ids1) and torch.equal(vals0, vals1)
+        h_now = hint.cpu().numpy()
+        assert np.all(np.isfinite(h_now)) and not torch.equal(before, hint)
+        # the carried values are lower bounds of this chunk's thresholds: tau_t >= k-th largest oracle value - rounding
+        o = orc.encode_topk(x[0], W[0], b[0], w.k, w.dtype, want_dense=True)
+        kth = o["zsel"][:, -1]
+        nx = np.linalg.norm(synth.storage_to_f64(x[0], w.dtype), axis=1)
+        assert h_now[0, 1] <= kth.min() * (1 + 1e-3) + 1e-6 and h_now[0, 0] <= (kth / nx).min() * (1 + 1e-3) + 1e-6
+        seen.append(h_now.copy())
+        for bad in (1e30, -1e30, float("nan")):
+            hb = torch.full_like(hint, bad)
+            ids2, vals2 = s3.sae_encode_topk_stream(xg, Wg, bg, w.k, hb)
+            torch.cuda.synchronize()
+            assert torch.equal(ids0, ids2) and torch.equal(vals0, vals2), bad
+    assert np.allclose(seen[1], seen[2], rtol=0.2)          # the statistic is stable from chunk to chunk
+    # shapes outside the threshold-carrying kernel: same results, hint untouched
+    w4 = synth.shrink(synth.WORKLOADS["c4_qwen7b"], L=200, T=200, n_feat=1000)
+    x, W4, b4 = parity.head_inputs(w4, [0])
+    h4 = s3.new_tau_hint(1)
+    a = s3.sae_encode_topk(parity.to_gpu(x, w4.dtype), parity.to_gpu(W4, w4.dtype), parity.to_gpu(b4, "fp32"), w4.k)
+    bb = s3.sae_encode_topk_stream(parity.to_gpu(x, w4.dtype), parity.to_gpu(W4, w4.dtype), parity.to_gpu(b4, "fp32"), w4.k, h4)
+    torch.cuda.synchronize()
+    assert torch.equal(a[0], bb[0]) and torch.equal(a[1], bb[1]) and torch.all(torch.isinf(h4))

@@ -23,26 +23,33 @@ def strided_ids(rng, rows, k, n_feat):
 
 
 def test_encode_full_launch_sampled_rows():
+    """Two consecutive chunks through the streamed call bench.py times (the second one starts from the thresholds
+    carried over from the first); sampled rows of both against the oracle."""
     import torch
     import paper_2601_17702_amd as s3
     w, H = W2, W2.n_heads
-    chunk = 3
     with ThreadPoolExecutor(16) as ex:
-        parts = list(ex.map(lambda h: (synth.gen_keys(w, h, chunk), synth.gen_w_enc(w, h), synth.gen_b_enc(w, h)), range(H)))
-    x = np.stack([p[0] for p in parts]); W = np.stack([p[1] for p in parts]); b = np.stack([p[2] for p in parts])
+        parts = list(ex.map(lambda h: (synth.gen_w_enc(w, h), synth.gen_b_enc(w, h)), range(H)))
+    W = np.stack([p[0] for p in parts]); b = np.stack([p[1] for p in parts])
+    Wg, bg = parity.to_gpu(W, w.dtype), parity.to_gpu(b, "fp32")
+    hint = s3.new_tau_hint(H)
     ids = torch.empty((H, w.T, w.k), dtype=torch.int32, device="cuda")
     vals = torch.empty((H, w.T, w.k), dtype=torch.float32, device="cuda")
-    s3.sae_encode_topk(parity.to_gpu(x, w.dtype), parity.to_gpu(W, w.dtype), parity.to_gpu(b, "fp32"), w.k, ids, vals)
-    torch.cuda.synchronize()
-    ids, vals = ids.cpu().numpy(), vals.cpu().numpy()
     heads = [0, 7, 8, 137, 255]
     toks = np.array([0, 1, 31, 32, 255, 256, 257, 1023, 1024, 1500, 2046, 2047])
-    ties, rows = parity.check_encode(ids[heads][:, toks], vals[heads][:, toks], x[heads][:, toks], W[heads], b[heads], w.k, w.dtype)
-    assert ties <= rows // 20
-    # properties of every row: distinct ids in range, values descending and non-negative
-    srt = np.sort(ids, axis=2)
-    assert srt.min() >= 0 and srt.max() < w.n_feat and np.all(np.diff(srt, axis=2) > 0)
-    assert np.all(np.diff(vals, axis=2) <= 0) and vals.min() >= 0
+    for chunk in (3, 4):
+        with ThreadPoolExecutor(16) as ex:
+            x = np.stack(list(ex.map(lambda h: synth.gen_keys(w, h, chunk), range(H))))
+        s3.sae_encode_topk_stream(parity.to_gpu(x, w.dtype), Wg, bg, w.k, hint, None, ids, vals)
+        torch.cuda.synchronize()
+        gi, gv = ids.cpu().numpy(), vals.cpu().numpy()
+        ties, rows = parity.check_encode(gi[heads][:, toks], gv[heads][:, toks], x[heads][:, toks], W[heads], b[heads], w.k, w.dtype)
+        assert ties <= rows // 20
+        # properties of every row: distinct ids in range, values descending and non-negative
+        srt = np.sort(gi, axis=2)
+        assert srt.min() >= 0 and srt.max() < w.n_feat and np.all(np.diff(srt, axis=2) > 0)
+        assert np.all(np.diff(gv, axis=2) <= 0) and gv.min() >= 0
+        assert torch.all(torch.isfinite(hint))
 
 
 def test_index_and_scores_full_size():
