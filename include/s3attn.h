@@ -72,9 +72,10 @@ int s3_sae_encode_topk(const void* x, int dtype, int T, int d_head, const void* 
  * call.  The k-th largest pre-activation of a token scales with |x_t|, so the smallest
  * tau_t / |x_t| (and the smallest tau_t) of one chunk are good starts for the next one.
  *
- *   tau_hint [n_heads][2] fp32, device, read and overwritten: lower bounds of tau_t / |x_t| and
- *            of tau_t over the tokens of the previous call.  Fill with -INFINITY before the
- *            first chunk of a stream (no bound: same work as s3_sae_encode_topk).
+ *   tau_hint [n_heads][2] fp32, device, read and overwritten: the smallest tau_t / |x_t| and the
+ *            smallest tau_t over the tokens of the previous call; only the one that was the tighter
+ *            predictor on that call is kept, the other is -INFINITY.  Fill with -INFINITY before
+ *            the first chunk of a stream (no bound: same work as s3_sae_encode_topk).
  *   ws       s3_sae_encode_topk_stream_workspace(n_heads, T) bytes, 256-byte aligned, device;
  *            scratch, contents meaningless between calls.
  * Shapes the threshold-carrying kernel is not built for (anything but bf16, d_head 128, k <= 32,

@@ -50,7 +50,7 @@ constexpr int kStageB = kFT * RB;
 constexpr int kBiasB = 256;      // the 64 fp32 biases of a pair of stages (one wavefront-wide copy)
 constexpr int CAPL = 40;         // list slots per lane (a token has two lanes)
 constexpr int kGuard = 4;        // appends possible between two fullness checks
-constexpr float kHintMargin = 0.02f;   // streamed calls start 2 % below the carried bound
+constexpr float kHintMargin = 0.03f;   // streamed calls start 3 % below the carried bound
 constexpr int kOffBias = kRing * kStageB;
 constexpr int kOffVote = kOffBias + (kRing / 2) * kBiasB;
 constexpr int kOffVal = kOffVote + 16;
@@ -328,10 +328,11 @@ __global__ __launch_bounds__(kThreads) void sae_encode_topk_fast_kernel(EncParam
         // carried bounds, lowered by a margin (a bound that is still too high only costs a redo of that token)
         const float hr = p.hint_in[2 * head], ha = p.hint_in[2 * head + 1];
         const float tr = hr > -INFINITY ? hr * xnorm : -INFINITY;
-        const float t0 = fmaxf(tr, ha);
+        const float t0 = fmaxf(tr, ha);             // one of the two is -inf (see enc_stream_post_kernel)
         tau = t0 > -INFINITY ? t0 - p.margin * fabsf(t0) : -INFINITY;
     }
     if (!tok_ok) tau = INFINITY;      // lanes without a token (ragged last tile, short redo list) collect nothing
+    const bool wave_active = __any(tok_ok);      // a wavefront without tokens only takes part in copies and barriers
     const int k = p.k;
     const int loose = min(k + (k >> 3) + 2, CAPL - kGuard);
     const int nst = p.n_feat / kFT;                                // a multiple of 4
@@ -517,7 +518,7 @@ __global__ __launch_bounds__(kThreads) void sae_encode_topk_fast_kernel(EncParam
         const int pp_ = (j >> 1) + (Q);                                                                      \
         S3_LOAD_PAIR(2 * pp_ + 2, (Q) ^ 1);                                                                  \
         S3_T(0)                                                                                              \
-        {                                                                                                    \
+        if (wave_active) {                                                                                   \
             S3_READS(2 * (Q))                                                                                \
             S3_MFMAS(acc0, acc1)                                                                             \
             S3_T(2)                                                                                          \
@@ -525,13 +526,13 @@ __global__ __launch_bounds__(kThreads) void sae_encode_topk_fast_kernel(EncParam
             S3_T(8)                                                                                          \
             if ((Q) != 0 || j > 0) S3_HITS(acc1, 2 * pp_ - 1);                                               \
         }                                                                                                    \
-        {                                                                                                    \
+        if (wave_active) {                                                                                   \
             S3_READS(2 * (Q) + 1)                                                                            \
             S3_MFMAS(acc1, acc0)                                                                             \
             S3_T(2)                                                                                          \
             S3_HITS(acc0, 2 * pp_);                                                                          \
+            S3_VOTE_CAST(pp_)                                                                                \
         }                                                                                                    \
-        S3_VOTE_CAST(pp_)                                                                                    \
         S3_T(3)                                                                                              \
         stage_barrier<0>();                                                                                  \
         S3_T(4)                                                                                              \
@@ -568,9 +569,24 @@ __global__ __launch_bounds__(kThreads) void sae_encode_topk_fast_kernel(EncParam
             r = fminf(r, __shfl_xor(r, d));
             a = fminf(a, __shfl_xor(a, d));
         }
+        // sums of tau, |x| and the token count: they tell which of the two bounds was the tighter one on this call
+        float s_tau = tok_ok && !failed && half == 0 ? tau : 0.f;
+        float s_x = tok_ok && !failed && half == 0 ? xnorm : 0.f;
+        float s_n = tok_ok && !failed && half == 0 ? 1.f : 0.f;
+#pragma unroll
+        for (int d = 16; d > 0; d >>= 1) {
+            s_tau += __shfl_xor(s_tau, d);
+            s_x += __shfl_xor(s_x, d);
+            s_n += __shfl_xor(s_n, d);
+        }
         if (lane == 0) {
             if (r < INFINITY) atomicMin(&p.hint_out[2 * head], ordered_key(r));
             if (a < INFINITY) atomicMin(&p.hint_out[2 * head + 1], ordered_key(a));
+            if (s_n > 0.f) {
+                atomicAdd(&p.hint_sum[3 * head], s_tau);
+                atomicAdd(&p.hint_sum[3 * head + 1], s_x);
+                atomicAdd(&p.hint_sum[3 * head + 2], s_n);
+            }
         }
     }
 
@@ -614,14 +630,27 @@ __global__ __launch_bounds__(kThreads) void sae_encode_topk_fast_kernel(EncParam
 }
 
 // Streamed calls: counters and this call's minima start empty; afterwards the minima become the carried bounds.
-__global__ void enc_stream_prep_kernel(int32_t* redo_cnt, unsigned* hint_out, int n_heads) {
+__global__ void enc_stream_prep_kernel(int32_t* redo_cnt, unsigned* hint_out, float* hint_sum, int n_heads) {
     const int i = blockIdx.x * blockDim.x + threadIdx.x;
     if (i < n_heads) redo_cnt[i] = 0;
     if (i < 2 * n_heads) hint_out[i] = 0xFFFFFFFFu;
+    if (i < 3 * n_heads) hint_sum[i] = 0.f;
 }
-__global__ void enc_stream_post_kernel(const unsigned* hint_out, float* hint, int n_heads) {
-    const int i = blockIdx.x * blockDim.x + threadIdx.x;
-    if (i < 2 * n_heads) hint[i] = hint_out[i] == 0xFFFFFFFFu ? -INFINITY : key_value(hint_out[i]);
+// Two candidate bounds per head: (smallest tau / |x|) * |x_t| and the smallest tau.  Which one predicts a token's
+// threshold better depends on the data (pre-activations dominated by W x scale with |x|, those dominated by the
+// bias do not); using both at once would fail whenever either overshoots.  The one that was tighter on average
+// over this call's tokens is carried, the other one is set to -inf.
+__global__ void enc_stream_post_kernel(const unsigned* hint_out, const float* hint_sum, float* hint, int n_heads) {
+    const int h = blockIdx.x * blockDim.x + threadIdx.x;
+    if (h >= n_heads) return;
+    const float r = hint_out[2 * h] == 0xFFFFFFFFu ? -INFINITY : key_value(hint_out[2 * h]);
+    const float a = hint_out[2 * h + 1] == 0xFFFFFFFFu ? -INFINITY : key_value(hint_out[2 * h + 1]);
+    const float s_tau = hint_sum[3 * h], s_x = hint_sum[3 * h + 1], s_n = hint_sum[3 * h + 2];
+    const float waste_r = r > -INFINITY ? s_tau - r * s_x : INFINITY;
+    const float waste_a = a > -INFINITY ? s_tau - a * s_n : INFINITY;
+    const bool use_r = waste_r <= waste_a;
+    hint[2 * h] = use_r ? r : -INFINITY;
+    hint[2 * h + 1] = use_r ? -INFINITY : a;
 }
 
 template <int ABL>
@@ -649,12 +678,13 @@ static int fast_dispatch(EncParams p, hipStream_t st);
 
 int s3_encode_fast_launch(EncParams p, hipStream_t st) {
     p.mode = 0;
-    p.hint_in = nullptr; p.hint_out = nullptr; p.redo_list = nullptr; p.redo_cnt = nullptr;
+    p.hint_in = nullptr; p.hint_out = nullptr; p.hint_sum = nullptr; p.redo_list = nullptr; p.redo_cnt = nullptr;
     return fast_dispatch(p, st);
 }
 
 size_t s3_encode_fast_stream_workspace(int n_heads, int T) {
-    return s3_align((size_t)n_heads * 4) + s3_align((size_t)n_heads * 8) + s3_align((size_t)n_heads * T * 4);
+    return s3_align((size_t)n_heads * 4) + s3_align((size_t)n_heads * 8) + s3_align((size_t)n_heads * 12) +
+           s3_align((size_t)n_heads * T * 4);
 }
 
 // Main pass from the carried bounds, redo pass (from -inf) for the tokens whose bound was too high, then this
@@ -663,10 +693,12 @@ int s3_encode_fast_stream(EncParams p, float* hint, void* ws, hipStream_t st) {
     char* base = (char*)ws;
     p.redo_cnt = (int32_t*)base;
     p.hint_out = (unsigned*)(base + s3_align((size_t)p.n_heads * 4));
-    p.redo_list = (int32_t*)(base + s3_align((size_t)p.n_heads * 4) + s3_align((size_t)p.n_heads * 8));
+    p.hint_sum = (float*)(base + s3_align((size_t)p.n_heads * 4) + s3_align((size_t)p.n_heads * 8));
+    p.redo_list = (int32_t*)(base + s3_align((size_t)p.n_heads * 4) + s3_align((size_t)p.n_heads * 8) +
+                             s3_align((size_t)p.n_heads * 12));
     p.hint_in = hint;
-    const int nb = (2 * p.n_heads + 255) / 256;
-    hipLaunchKernelGGL(enc_stream_prep_kernel, dim3(nb), dim3(256), 0, st, p.redo_cnt, p.hint_out, p.n_heads);
+    const int nb = (3 * p.n_heads + 255) / 256;
+    hipLaunchKernelGGL(enc_stream_prep_kernel, dim3(nb), dim3(256), 0, st, p.redo_cnt, p.hint_out, p.hint_sum, p.n_heads);
     p.margin = (float)env_int("S3_ENC_MARGIN", (int)(kHintMargin * 1000.f + 0.5f)) * 1e-3f;   // per mille, tuning
     p.mode = 1;
     int rc = fast_dispatch(p, st);
@@ -674,7 +706,7 @@ int s3_encode_fast_stream(EncParams p, float* hint, void* ws, hipStream_t st) {
     p.mode = 2;
     rc = fast_dispatch(p, st);
     if (rc) return rc;
-    hipLaunchKernelGGL(enc_stream_post_kernel, dim3(nb), dim3(256), 0, st, p.hint_out, hint, p.n_heads);
+    hipLaunchKernelGGL(enc_stream_post_kernel, dim3(nb), dim3(256), 0, st, p.hint_out, p.hint_sum, hint, p.n_heads);
     S3_HIP(hipGetLastError());
     return S3_OK;
 }

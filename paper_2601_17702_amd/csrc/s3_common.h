@@ -41,6 +41,7 @@ struct EncParams {
     int mode;                  // 0 plain, 1 start from the carried bound, 2 redo the tokens listed in redo_list
     const float* hint_in;      // [n_heads][2]: lower bounds of tau / |x| and of tau seen in the previous call
     unsigned* hint_out;        // [n_heads][2]: ordered keys of this call's minima (atomicMin)
+    float* hint_sum;           // [n_heads][3]: sums of tau, |x| and the token count over this call
     int32_t* redo_list;        // [n_heads][T] tokens whose carried bound was too high
     int32_t* redo_cnt;         // [n_heads]
 };

@@ -131,19 +131,20 @@ def test_streamed_calls_equal_plain_calls_whatever_the_carried_threshold_holds()
         torch.cuda.synchronize()
         assert torch.equal(ids0, ids1) and torch.equal(vals0, vals1)
         h_now = hint.cpu().numpy()
-        assert np.all(np.isfinite(h_now)) and not torch.equal(before, hint)
+        assert np.all(np.isfinite(h_now).sum(axis=1) == 1) and not torch.equal(before, hint)   # one bound per head is carried
         # the carried values are lower bounds of this chunk's thresholds: tau_t >= k-th largest oracle value - rounding
         o = orc.encode_topk(x[0], W[0], b[0], w.k, w.dtype, want_dense=True)
         kth = o["zsel"][:, -1]
         nx = np.linalg.norm(synth.storage_to_f64(x[0], w.dtype), axis=1)
         assert h_now[0, 1] <= kth.min() * (1 + 1e-3) + 1e-6 and h_now[0, 0] <= (kth / nx).min() * (1 + 1e-3) + 1e-6
+        assert np.isfinite(h_now[0, 0])                        # W x dominates here: the |x|-scaled bound is the tighter one
         seen.append(h_now.copy())
         for bad in (1e30, -1e30, float("nan")):
             hb = torch.full_like(hint, bad)
             ids2, vals2 = s3.sae_encode_topk_stream(xg, Wg, bg, w.k, hb)
             torch.cuda.synchronize()
             assert torch.equal(ids0, ids2) and torch.equal(vals0, vals2), bad
-    assert np.allclose(seen[1], seen[2], rtol=0.2)          # the statistic is stable from chunk to chunk
+    assert np.allclose(seen[1][:, 0], seen[2][:, 0], rtol=0.2)          # the statistic is stable from chunk to chunk
     # shapes outside the threshold-carrying kernel: same results, hint untouched
     w4 = synth.shrink(synth.WORKLOADS["c4_qwen7b"], L=200, T=200, n_feat=1000)
     x, W4, b4 = parity.head_inputs(w4, [0])
