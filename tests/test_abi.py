@@ -47,4 +47,12 @@ def test_host_side_argument_validation():
     assert L.s3_index_build(one, None, 8, 4, 64, one, one, one, 16, None) == -3          # workspace too small
     assert L.s3_index_build_workspace(8, 4, 64) > 0 and L.s3_index_build_workspace(8, 65, 64) == 0
     assert L.s3_coactivate_score(None, one, one, 1, 10, 4, 2, 0, 1, None, one, one, one, one, 1 << 20, None) == -1
+    need = L.s3_sae_encode_topk_stream_workspace(2, 512)
+    assert need >= 2 * 512 * 4 and L.s3_sae_encode_topk_stream_workspace(0, 512) == 0
+    args = (one, 0, 512, 128, one, one, 2048, 32, 2, one, one)
+    assert L.s3_sae_encode_topk_stream(*args, None, one, need, None) == -1                 # null tau_hint
+    assert L.s3_sae_encode_topk_stream(*args, one, None, need, None) == -1                 # null workspace
+    assert L.s3_sae_encode_topk_stream(*args, one, C.c_void_p(264), need, None) == -1      # workspace alignment
+    assert L.s3_sae_encode_topk_stream(*args, one, one, need - 1, None) == -3              # workspace too small
+    assert b"s3_sae_encode_topk_stream" in L.s3_last_error()
     assert s3.MAX_K == 64 and s3.MAX_FEAT == 65536
