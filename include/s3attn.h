@@ -78,7 +78,7 @@ int s3_sae_encode_topk(const void* x, int dtype, int T, int d_head, const void* 
  *            the first chunk of a stream (no bound: same work as s3_sae_encode_topk).
  *   ws       s3_sae_encode_topk_stream_workspace(n_heads, T) bytes, 256-byte aligned, device;
  *            scratch, contents meaningless between calls.
- * Shapes the threshold-carrying kernel is not built for (anything but bf16, d_head 128, k <= 32,
+ * Shapes the threshold-carrying kernel is not built for (anything but bf16, d_head 128,
  * n_feat % 128 == 0) run exactly as s3_sae_encode_topk and leave tau_hint untouched.
  * Errors as s3_sae_encode_topk; S3_ECAPACITY if ws_bytes is too small. */
 size_t s3_sae_encode_topk_stream_workspace(int n_heads, int T);

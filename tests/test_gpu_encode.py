@@ -145,6 +145,21 @@ def test_streamed_calls_equal_plain_calls_whatever_the_carried_threshold_holds()
             torch.cuda.synchronize()
             assert torch.equal(ids0, ids2) and torch.equal(vals0, vals2), bad
     assert np.allclose(seen[1][:, 0], seen[2][:, 0], rtol=0.2)          # the statistic is stable from chunk to chunk
+    # the k <= 64 build of the kernel (4 wavefronts per workgroup, one token per sort step), streamed as well
+    w4 = synth.shrink(synth.WORKLOADS["c4_qwen7b"], L=2 * 300, T=300, n_feat=4096)
+    W4, b4 = np.stack([synth.gen_w_enc(w4, h) for h in (0, 1)]), np.stack([synth.gen_b_enc(w4, h) for h in (0, 1)])
+    W4g, b4g = parity.to_gpu(W4, w4.dtype), parity.to_gpu(b4, "fp32")
+    h4 = s3.new_tau_hint(2)
+    for c in range(w4.n_chunks):
+        x = np.stack([synth.gen_keys(w4, h, c) for h in (0, 1)])
+        xg = parity.to_gpu(x, w4.dtype)
+        a0 = s3.sae_encode_topk(xg, W4g, b4g, w4.k)
+        a1 = s3.sae_encode_topk_stream(xg, W4g, b4g, w4.k, h4)
+        a2 = s3.sae_encode_topk_stream(xg, W4g, b4g, w4.k, torch.full_like(h4, 1e30))
+        torch.cuda.synchronize()
+        assert torch.equal(a0[0], a1[0]) and torch.equal(a0[1], a1[1]) and torch.equal(a0[0], a2[0]) and torch.equal(a0[1], a2[1])
+        ties, rows = parity.check_encode(a1[0].cpu().numpy(), a1[1].cpu().numpy(), x, W4, b4, w4.k, w4.dtype)
+        assert ties <= rows // 10
     # shapes outside the threshold-carrying kernel: same results, hint untouched
     w4 = synth.shrink(synth.WORKLOADS["c4_qwen7b"], L=200, T=200, n_feat=1000)
     x, W4, b4 = parity.head_inputs(w4, [0])
