@@ -205,7 +205,7 @@ class Index:
         return starts, scores, found, S
 
     def destroy(self):
-        if getattr(self, "_h", None):
+        if getattr(self, "_h", None) and lib is not None:    # module globals are gone at interpreter shutdown
             lib().s3_index_destroy(self._h)
             self._h = None
 

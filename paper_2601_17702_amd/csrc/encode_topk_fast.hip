@@ -63,19 +63,8 @@ constexpr int kNoHits = 1, kProfile = 16;
 // kProfile build: cycles per phase, summed over the steps of wavefronts 0 and 4 of workgroup 0
 __device__ unsigned long long s3_prof[32];
 
-__device__ __forceinline__ void lds_store_f32(unsigned addr, float v) {
-    asm volatile("ds_write_b32 %0, %1" ::"v"(addr), "v"(v) : "memory");
-}
-__device__ __forceinline__ void lds_store_u16(unsigned addr, unsigned v) {
-    asm volatile("ds_write_b16 %0, %1" ::"v"(addr), "v"(v) : "memory");
-}
 __device__ __forceinline__ void lds_store_u32(unsigned addr, unsigned v) {
     asm volatile("ds_write_b32 %0, %1" ::"v"(addr), "v"(v) : "memory");
-}
-__device__ __forceinline__ unsigned lds_load_u32(unsigned addr) {
-    unsigned v;
-    asm volatile("ds_read_b32 %0, %1\n\ts_waitcnt lgkmcnt(0)" : "=&v"(v) : "v"(addr) : "memory");
-    return v;
 }
 
 // Waits until at most N of this wavefront's global->LDS copies are in flight and all its LDS accesses are

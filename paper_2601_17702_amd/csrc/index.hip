@@ -39,47 +39,65 @@ struct IdxDev {
     const int32_t* pos_log;   // [max_tokens] absolute position of each appended row
     int64_t inter_stride, piece_stride, off_stride, pos_stride;
     int n_feat, k, S, NB, nbB, ptok, tile_post, max_tiles;
+    uint32_t kinv;        // ceil(2^32 / k) for k > 1: i / k == umulhi(i, kinv) for every posting index of a tile
 };
 
-// Exclusive prefix sum of one int per thread over the block, in thread order.
+// Inclusive prefix sums over the lanes of a wavefront / over each row of 16 lanes, by data-parallel-primitive
+// lane shifts: row_shr 1, 2, 4, 8 inside the rows, then lane 15 of a row into the next row, lane 31 into rows 2, 3.
+__device__ __forceinline__ int row_incl_scan(int x) {
+    x += __builtin_amdgcn_update_dpp(0, x, 0x111, 0xf, 0xf, false);
+    x += __builtin_amdgcn_update_dpp(0, x, 0x112, 0xf, 0xf, false);
+    x += __builtin_amdgcn_update_dpp(0, x, 0x114, 0xf, 0xf, false);
+    x += __builtin_amdgcn_update_dpp(0, x, 0x118, 0xf, 0xf, false);
+    return x;
+}
+__device__ __forceinline__ int wave_incl_scan(int x) {
+    x = row_incl_scan(x);
+    x += __builtin_amdgcn_update_dpp(0, x, 0x142, 0xa, 0xf, false);
+    x += __builtin_amdgcn_update_dpp(0, x, 0x143, 0xc, 0xf, false);
+    return x;
+}
+
+// Exclusive prefix sum of one int per thread over the block, in thread order.  wsum: one int per wavefront.
 template <int NT>
 __device__ __forceinline__ int block_excl_scan(int v, int* wsum, int& total) {
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    int x = v;
-#pragma unroll
-    for (int o = 1; o < 64; o <<= 1) {
-        int y = __shfl_up(x, o);
-        if (lane >= o) x += y;
-    }
+    constexpr int NW = NT / 64;
+    static_assert(NW == 4 || NW == 16, "wavefront sums are scanned inside one row of 16 lanes");
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int x = wave_incl_scan(v);
     if (lane == 63) wsum[wave] = x;
     __syncthreads();
-    int base = 0, tot = 0;
-#pragma unroll
-    for (int w = 0; w < NT / 64; ++w) {
-        int s = wsum[w];
-        if (w < wave) base += s;
-        tot += s;
-    }
+    const int s = row_incl_scan(wsum[lane & (NW - 1)]);     // lanes 0 .. NW-1: sums of wavefronts 0 .. lane
     __syncthreads();
-    total = tot;
+    total = __builtin_amdgcn_readlane(s, NW - 1);
+    const int base = wave ? __builtin_amdgcn_readlane(s, wave - 1) : 0;
     return base + x - v;
 }
 
-// Lanes of the wavefront whose (valid) key has the same low `nbits` bits as this lane's: one ballot per bit.
-__device__ __forceinline__ unsigned long long same_key_lanes(unsigned key, int nbits, bool valid) {
-    unsigned long long p = __ballot(valid);
-    for (int bit = 0; bit < nbits; ++bit) {
-        const bool one = (key >> bit) & 1u;
-        const unsigned long long b = __ballot(valid && one);
-        p &= one ? b : ~b;
+// Wavefront-wide match on the low NBITS bits of `key`, one ballot per bit.  For a valid lane, bits 0..6 of the
+// result hold the number of valid lanes with the same key and bits 8..13 the number of those in lower lanes; an
+// invalid lane gets 0.  Invalid lanes pass key 0; key bits at and above NBITS must be 0.
+template <int NBITS>
+__device__ __forceinline__ unsigned match_lanes(unsigned key, bool valid) {
+    const unsigned long long v = __ballot(valid);
+    unsigned lo = (unsigned)v, hi = (unsigned)(v >> 32);
+#pragma unroll
+    for (int bit = 0; bit < NBITS; ++bit) {
+        const int m = (int)(key << (31 - bit)) >> 31;           // all ones when the bit is set
+        const unsigned long long b = __ballot(m != 0);
+        lo &= ~((unsigned)b ^ (unsigned)m);                      // keep the lanes whose bit equals mine
+        hi &= ~((unsigned)(b >> 32) ^ (unsigned)m);
     }
-    return valid ? p : 0ull;
+    const unsigned before = __builtin_amdgcn_mbcnt_hi(hi, __builtin_amdgcn_mbcnt_lo(lo, 0u));
+    const unsigned total = (unsigned)(__popc(lo) + __popc(hi));
+    return valid ? (total | (before << 8)) : 0u;
 }
 
 // Stable multi-way split of up to kWaves * kRounds * 64 keyed entries by a digit of at most 8 bits.
 // Wavefront w owns the entries [w seg, (w + 1) seg) in rounds of 64 (lane order = entry order).  Inside a round
 // the lanes that share a digit find each other with ballots; the first of them adds their number to the
-// wavefront's own counter row, so no atomics are needed and the order of equal digits is the entry order.
+// wavefront's own counter row, so nothing depends on an ordering of atomics and equal digits keep the entry order.
 //   count   : cnt[w][digit] += lanes with that digit                      (split_count)
 //   scan    : exclusive prefix over (digit major, wavefront minor)        (split_scan)
 //   rank    : cnt[w][digit] (now a running base) + lanes before me        (split_rank)
@@ -87,8 +105,10 @@ constexpr int kSplitThreads = 1024;
 constexpr int kSplitWaves = kSplitThreads / 64;
 constexpr int kSplitRounds = 8;          // 16 wavefronts x 8 rounds x 64 lanes = 8192 entries per pass
 
-__device__ __forceinline__ void split_count(int* cnt_row, unsigned digit, unsigned long long peers, int lane) {
-    if (peers && (peers & ((1ull << lane) - 1ull)) == 0) cnt_row[digit] += __popcll(peers);
+// `m` = match_lanes() result | digit << 16.  The first lane of each group of equal digits adds the group's size
+// to the wavefront's own counter row: one writer per counter, so the sum does not depend on any ordering.
+__device__ __forceinline__ void split_count(int* cnt_row, unsigned m) {
+    if ((m & 0xFFu) && !(m & 0x3F00u)) atomicAdd(&cnt_row[m >> 16], (int)(m & 0xFFu));
 }
 
 // cnt: [kSplitWaves][nd] counts -> running bases; dstart[d] / dcount[d]: first rank and number of entries of digit d
@@ -114,24 +134,26 @@ __device__ __forceinline__ void split_scan(int* cnt, int nd, int* dstart, int* d
         }
     }
     // the kSplitWaves / per threads of a digit are adjacent lanes: their sum is the digit's count
+    static_assert(kSplitWaves / per == 4, "a digit's threads are one aligned group of four lanes");
     int dc = s;
-#pragma unroll
-    for (int o = 1; o < kSplitWaves / per; o <<= 1) dc += __shfl_xor(dc, o);
+    dc += __builtin_amdgcn_update_dpp(0, dc, 0xB1, 0xf, 0xf, false);     // lanes 1 0 3 2 of each group of four
+    dc += __builtin_amdgcn_update_dpp(0, dc, 0x4E, 0xf, 0xf, false);     // lanes 2 3 0 1
     if (d < nd && w0 == 0) { dstart[d] = ex; dcount[d] = dc; }
     __syncthreads();
 }
 
-__device__ __forceinline__ int split_rank(int* cnt_row, unsigned digit, unsigned long long peers, int lane) {
+__device__ __forceinline__ int split_rank(int* cnt_row, unsigned m) {
+    const unsigned tot = m & 0xFFu, before = (m >> 8) & 0x3Fu;
     int r = 0;
-    if (peers) r = cnt_row[digit] + __popcll(peers & ((1ull << lane) - 1ull));
-    if (peers && (peers & ((1ull << lane) - 1ull)) == 0) cnt_row[digit] = r + __popcll(peers);
-    return r;
+    if (tot) r = cnt_row[m >> 16];
+    if (tot && before == 0) cnt_row[m >> 16] = r + (int)tot;     // same wavefront, after the group's reads
+    return r + (int)before;
 }
 
 // One tile of <= tile_post postings of one head: split by bucket, write the tile and its piece table.
 // `src` is the first row of tile `tile0` (row stride k, head stride head_stride elements).
-__global__ __launch_bounds__(kSplitThreads) void idx_partition_kernel(const int32_t* src, int64_t head_stride,
-                                                                      int rows_avail, int tile0, IdxDev d) {
+__global__ __launch_bounds__(kSplitThreads, 8) void idx_partition_kernel(const int32_t* src, int64_t head_stride,
+                                                                         int rows_avail, int tile0, IdxDev d) {
     __shared__ int cnt[kSplitWaves * 256];
     __shared__ uint32_t stage[kTilePost];
     __shared__ int wsum[kSplitWaves];
@@ -151,24 +173,24 @@ __global__ __launch_bounds__(kSplitThreads) void idx_partition_kernel(const int3
     __syncthreads();
     int* row = cnt + wave * nd;
     uint32_t word[kSplitRounds];
-    unsigned dig[kSplitRounds];
-    unsigned long long peers[kSplitRounds];
+    unsigned meta[kSplitRounds];       // match_lanes() | bucket << 16
 #pragma unroll
     for (int r = 0; r < kSplitRounds; ++r) {
-        const int i = (wave * kSplitRounds + r) * 64 + lane;
-        const bool valid = i < n;
+        const uint32_t i = (uint32_t)((wave * kSplitRounds + r) * 64 + lane);
+        const bool valid = (int)i < n;
         const uint32_t id = valid ? (uint32_t)s[i] : 0u;
-        dig[r] = min(id >> d.S, (uint32_t)(nd - 1));     // ids are < n_feat by contract; never index past the counters
-        word[r] = ((row0 + (uint32_t)(i / d.k)) << d.S) | (id & mask);
-        peers[r] = same_key_lanes(dig[r], d.nbB, valid);
-        split_count(row, dig[r], peers[r], lane);
+        const uint32_t dg = min(id >> d.S, (uint32_t)(nd - 1));   // ids are < n_feat by contract; never index past the counters
+        const uint32_t trow = d.k > 1 ? __umulhi(i, d.kinv) : i;
+        word[r] = ((row0 + trow) << d.S) | (id & mask);
+        meta[r] = match_lanes<8>(dg, valid) | (dg << 16);
+        split_count(row, meta[r]);
     }
     __syncthreads();
     split_scan(cnt, nd, bstart, bcount, wsum);
 #pragma unroll
     for (int r = 0; r < kSplitRounds; ++r) {
-        const int rk = split_rank(row, dig[r], peers[r], lane);
-        if (peers[r]) stage[rk] = word[r];
+        const int rk = split_rank(row, meta[r]);
+        if (meta[r] & 0xFFu) stage[rk] = word[r];
     }
     __syncthreads();
     uint32_t* out = d.inter + (size_t)head * d.inter_stride + (size_t)tile * d.tile_post;
@@ -207,11 +229,12 @@ __global__ __launch_bounds__(256) void idx_bucket_scan_kernel(IdxDev d) {
 // A bucket of at most kSortCap postings (the usual case) is done in one round: its sorted positions are
 // staged in LDS and written as one contiguous run.  A larger bucket (a very frequent feature) is counted
 // first and then taken in rounds of whole pieces, each round writing behind per-feature cursors.
-__global__ __launch_bounds__(kSplitThreads) void idx_bucket_sort_kernel(IdxDev d, int n_tiles) {
+template <int NBITS>
+__global__ __launch_bounds__(kSplitThreads, 8) void idx_bucket_sort_kernel(IdxDev d, int n_tiles) {
     extern __shared__ __align__(16) uint32_t dyn[];
-    uint32_t* bufa = dyn;                          // [kSortCap] gathered entries
-    int32_t* bufb = (int32_t*)(dyn + kSortCap);    // [kSortCap] sorted positions (single-round buckets)
-    int* pref = (int*)(dyn + 2 * kSortCap);        // [kSplitThreads + 1]
+    uint32_t* bufa = dyn;                          // [kSortCap] gathered entries of the round; once every wavefront
+    int32_t* bufb = (int32_t*)dyn;                 // holds its entries in registers: the sorted positions (same memory)
+    int* pref = (int*)(dyn + kSortCap);            // [kSplitThreads + 1]
     uint32_t* pinfo = (uint32_t*)(pref + kSplitThreads + 1);   // [kSplitThreads] piece words of the round
     int* wsum = (int*)(pinfo + kSplitThreads);     // [16]
     int* hist = wsum + 16;                         // [256] whole-bucket counts (before the first round only)
@@ -297,20 +320,21 @@ __global__ __launch_bounds__(kSplitThreads) void idx_bucket_sort_kernel(IdxDev d
 
         int* row = cnt + wave * nd;
         const int seg = ((n_r + kSplitWaves - 1) / kSplitWaves + 63) & ~63;      // entries per wavefront (<= 512)
-        uint32_t ent[kSplitRounds];
-        unsigned long long peers[kSplitRounds];
+        int32_t pos[kSplitRounds];
+        unsigned meta[kSplitRounds];       // match_lanes() | low feature bits << 16
 #pragma unroll
         for (int r = 0; r < kSplitRounds; ++r) {
             if (r * 64 >= seg) {          // uniform: this round is past the wavefront's share
-                ent[r] = 0u;
-                peers[r] = 0ull;
+                pos[r] = 0;
+                meta[r] = 0u;
                 continue;
             }
             const int i = wave * seg + r * 64 + lane;
             const bool valid = i < n_r;
-            ent[r] = valid ? bufa[i] : 0u;
-            peers[r] = same_key_lanes(ent[r] & mask, d.S, valid);
-            split_count(row, ent[r] & mask, peers[r], lane);
+            const uint32_t e = valid ? bufa[i] : 0u;
+            pos[r] = valid ? d.pos_log[e >> d.S] : 0;       // needed only after the scan: the load has time to land
+            meta[r] = match_lanes<NBITS>(e & mask, valid) | ((e & mask) << 16);
+            split_count(row, meta[r]);
         }
         __syncthreads();
         split_scan(cnt, nd, rstart, rcount, wsum);
@@ -318,12 +342,11 @@ __global__ __launch_bounds__(kSplitThreads) void idx_bucket_sort_kernel(IdxDev d
 #pragma unroll
         for (int r = 0; r < kSplitRounds; ++r) {
             if (r * 64 >= seg) continue;
-            const unsigned fl = ent[r] & mask;
-            const int rk = split_rank(row, fl, peers[r], lane);
-            if (peers[r]) {
-                const int32_t pos = d.pos_log[ent[r] >> d.S];
-                if (multi) posout[cursor[fl] + (rk - rstart[fl])] = pos;
-                else bufb[rk] = pos;
+            const int rk = split_rank(row, meta[r]);
+            if (meta[r] & 0xFFu) {
+                const unsigned fl = meta[r] >> 16;
+                if (multi) posout[cursor[fl] + (rk - rstart[fl])] = pos[r];
+                else bufb[rk] = pos[r];
             }
         }
         __syncthreads();
@@ -343,7 +366,7 @@ __global__ void idx_fill_positions_kernel(int32_t* dst, int n, int32_t base) {
 }
 
 size_t bucket_sort_lds(int S) {
-    return (size_t)2 * kSortCap * 4 + (kSplitThreads + 1) * 4 + kSplitThreads * 4 + 16 * 4 + 3 * 256 * 4 +
+    return (size_t)kSortCap * 4 + (kSplitThreads + 1) * 4 + kSplitThreads * 4 + 16 * 4 + 3 * 256 * 4 +
            ((size_t)kSplitWaves << S) * 4;
 }
 
@@ -373,16 +396,14 @@ int run_partition(const int32_t* src, int64_t head_stride, int rows, int tile0, 
 }
 
 int run_finalize(const IdxDev& d, int n_heads, int n_tiles, hipStream_t st) {
-    static bool attr_set = false;
-    if (!attr_set) {
-        S3_HIP(hipFuncSetAttribute((const void*)idx_bucket_sort_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                   (int)bucket_sort_lds(8)));
-        attr_set = true;
-    }
     hipLaunchKernelGGL(idx_totals_kernel, dim3(d.NB, n_heads), dim3(256), 0, st, d, n_tiles);
     hipLaunchKernelGGL(idx_bucket_scan_kernel, dim3(n_heads), dim3(256), 0, st, d);
-    hipLaunchKernelGGL(idx_bucket_sort_kernel, dim3(d.NB, n_heads), dim3(kSplitThreads), bucket_sort_lds(d.S), st, d,
-                       n_tiles);
+    // one ballot per low feature bit: the widths that the supported SAE sizes use most get their own build
+    const dim3 grid(d.NB, n_heads), block(kSplitThreads);
+    const size_t lds = bucket_sort_lds(d.S);       // < 64 KB: two workgroups per compute unit
+    if (d.S <= 6) hipLaunchKernelGGL(idx_bucket_sort_kernel<6>, grid, block, lds, st, d, n_tiles);
+    else if (d.S == 7) hipLaunchKernelGGL(idx_bucket_sort_kernel<7>, grid, block, lds, st, d, n_tiles);
+    else hipLaunchKernelGGL(idx_bucket_sort_kernel<8>, grid, block, lds, st, d, n_tiles);
     S3_HIP(hipGetLastError());
     return S3_OK;
 }
@@ -429,6 +450,7 @@ int s3_index_create(int n_heads, int n_feat, int k, int64_t max_tokens, s3_index
     ix->finalized = false; ix->sorted = true; ix->last_pos = -1; ix->g = g;
     IdxDev& d = ix->d;
     d.n_feat = n_feat; d.k = k; d.S = g.S; d.NB = g.NB; d.nbB = g.nbB; d.ptok = g.ptok; d.tile_post = g.tile_post;
+    d.kinv = k > 1 ? (uint32_t)(((1ull << 32) + (uint32_t)k - 1) / (uint32_t)k) : 0u;
     d.max_tiles = (int)((max_tokens + g.ptok - 1) / g.ptok);
     d.inter_stride = (int64_t)d.max_tiles * g.tile_post;
     d.piece_stride = (int64_t)g.NB * d.max_tiles;
@@ -604,6 +626,7 @@ int s3_index_build(const int32_t* ids, const int32_t* positions, int T, int k, i
     char* base = (char*)ws;
     IdxDev d;
     d.n_feat = n_feat; d.k = k; d.S = g.S; d.NB = g.NB; d.nbB = g.nbB; d.ptok = g.ptok; d.tile_post = g.tile_post;
+    d.kinv = k > 1 ? (uint32_t)(((1ull << 32) + (uint32_t)k - 1) / (uint32_t)k) : 0u;
     d.max_tiles = (T + g.ptok - 1) / g.ptok;
     d.inter = (uint32_t*)(base + off[0]); d.piece = (uint32_t*)(base + off[1]);
     d.total = (int32_t*)(base + off[2]); d.bbase = (int32_t*)(base + off[3]);
