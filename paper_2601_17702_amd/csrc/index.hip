@@ -62,7 +62,7 @@ __device__ __forceinline__ int wave_incl_scan(int x) {
 template <int NT>
 __device__ __forceinline__ int block_excl_scan(int v, int* wsum, int& total) {
     constexpr int NW = NT / 64;
-    static_assert(NW == 4 || NW == 16, "wavefront sums are scanned inside one row of 16 lanes");
+    static_assert(NW == 4 || NW == 8 || NW == 16, "wavefront sums are scanned inside one row of 16 lanes");
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int x = wave_incl_scan(v);
@@ -75,40 +75,49 @@ __device__ __forceinline__ int block_excl_scan(int v, int* wsum, int& total) {
     return base + x - v;
 }
 
-// Wavefront-wide match on the low NBITS bits of `key`, one ballot per bit.  For a valid lane, bits 0..6 of the
-// result hold the number of valid lanes with the same key and bits 8..13 the number of those in lower lanes; an
-// invalid lane gets 0.  Invalid lanes pass key 0; key bits at and above NBITS must be 0.
+// Stable multi-way split of up to kSplitWaves * kSplitRounds * 64 keyed entries by a digit of at most 8 bits.
+// Wavefront w owns the entries [w seg, (w + 1) seg) in rounds of 64 (lane order = entry order).
+//   count   : split_round() per round: the lanes that share a digit find each other with one ballot per digit bit;
+//             the first of them adds their number to the wavefront's own counter row (one writer per counter and
+//             instruction, so nothing depends on an ordering of atomics), every lane reads the counter back and so
+//             knows its rank among the wavefront's entries of that digit, this round and the earlier ones
+//   scan    : split_scan(): exclusive prefix over (digit major, wavefront minor) turns the counters into bases
+//   rank    : split_rank(): base of (wavefront, digit) + rank inside the wavefront
+constexpr int kSplitThreads = 1024;
+constexpr int kSplitWaves = kSplitThreads / 64;
+constexpr int kSplitRounds = 8;          // 16 wavefronts x 8 rounds x 64 lanes = 8192 entries per pass
+constexpr int kSplitOcc = 8;             // wavefronts per SIMD the kernels are built for: two workgroups per compute unit
+constexpr unsigned kSplitValid = 1u << 31;
+
+// One round for this lane's entry with digit `dg` (low NBITS bits, the rest 0; 0 on an invalid lane).  Returns
+// dg | rank inside the wavefront << 8 | kSplitValid, or 0 for an invalid lane.
 template <int NBITS>
-__device__ __forceinline__ unsigned match_lanes(unsigned key, bool valid) {
+__device__ __forceinline__ unsigned split_round(int* cnt_row, unsigned dg, bool valid) {
     const unsigned long long v = __ballot(valid);
     unsigned lo = (unsigned)v, hi = (unsigned)(v >> 32);
 #pragma unroll
     for (int bit = 0; bit < NBITS; ++bit) {
-        const int m = (int)(key << (31 - bit)) >> 31;           // all ones when the bit is set
+        int m = (int)(dg << (31 - bit)) >> 31;                  // all ones when the bit is set
+        asm volatile("" : "+v"(m));                             // one bit-field extract serves the ballot and the select
         const unsigned long long b = __ballot(m != 0);
-        lo &= ~((unsigned)b ^ (unsigned)m);                      // keep the lanes whose bit equals mine
-        hi &= ~((unsigned)(b >> 32) ^ (unsigned)m);
+        // keep the lanes whose bit equals mine: x & ~(b ^ m) as one three-input bit operation (table 0x90)
+        lo = __builtin_amdgcn_bitop3_b32(lo, (unsigned)b, (unsigned)m, 0x90);
+        hi = __builtin_amdgcn_bitop3_b32(hi, (unsigned)(b >> 32), (unsigned)m, 0x90);
     }
-    const unsigned before = __builtin_amdgcn_mbcnt_hi(hi, __builtin_amdgcn_mbcnt_lo(lo, 0u));
-    const unsigned total = (unsigned)(__popc(lo) + __popc(hi));
-    return valid ? (total | (before << 8)) : 0u;
+    const unsigned before = __builtin_amdgcn_mbcnt_hi(hi, __builtin_amdgcn_mbcnt_lo(lo, 0u));   // equal digits in lower lanes
+    const unsigned total = (unsigned)(__popc(lo) + __popc(hi));                                  // equal digits in the round
+    unsigned res = 0u;
+    if (valid) {
+        if (before == 0) atomicAdd(&cnt_row[dg], (int)total);
+        // the wavefront's LDS accesses execute in program order: this read sees the group's add
+        const unsigned after = (unsigned)cnt_row[dg];
+        res = dg | ((after - total + before) << 8) | kSplitValid;
+    }
+    return res;
 }
 
-// Stable multi-way split of up to kWaves * kRounds * 64 keyed entries by a digit of at most 8 bits.
-// Wavefront w owns the entries [w seg, (w + 1) seg) in rounds of 64 (lane order = entry order).  Inside a round
-// the lanes that share a digit find each other with ballots; the first of them adds their number to the
-// wavefront's own counter row, so nothing depends on an ordering of atomics and equal digits keep the entry order.
-//   count   : cnt[w][digit] += lanes with that digit                      (split_count)
-//   scan    : exclusive prefix over (digit major, wavefront minor)        (split_scan)
-//   rank    : cnt[w][digit] (now a running base) + lanes before me        (split_rank)
-constexpr int kSplitThreads = 1024;
-constexpr int kSplitWaves = kSplitThreads / 64;
-constexpr int kSplitRounds = 8;          // 16 wavefronts x 8 rounds x 64 lanes = 8192 entries per pass
-
-// `m` = match_lanes() result | digit << 16.  The first lane of each group of equal digits adds the group's size
-// to the wavefront's own counter row: one writer per counter, so the sum does not depend on any ordering.
-__device__ __forceinline__ void split_count(int* cnt_row, unsigned m) {
-    if ((m & 0xFFu) && !(m & 0x3F00u)) atomicAdd(&cnt_row[m >> 16], (int)(m & 0xFFu));
+__device__ __forceinline__ int split_rank(const int* cnt_row, unsigned m) {
+    return cnt_row[m & 0xFFu] + (int)((m >> 8) & 0x3FFFu);
 }
 
 // cnt: [kSplitWaves][nd] counts -> running bases; dstart[d] / dcount[d]: first rank and number of entries of digit d
@@ -134,25 +143,17 @@ __device__ __forceinline__ void split_scan(int* cnt, int nd, int* dstart, int* d
         }
     }
     // the kSplitWaves / per threads of a digit are adjacent lanes: their sum is the digit's count
-    static_assert(kSplitWaves / per == 4, "a digit's threads are one aligned group of four lanes");
+    static_assert(kSplitWaves / per == 2 || kSplitWaves / per == 4, "a digit's threads are an aligned group of 2 or 4 lanes");
     int dc = s;
     dc += __builtin_amdgcn_update_dpp(0, dc, 0xB1, 0xf, 0xf, false);     // lanes 1 0 3 2 of each group of four
-    dc += __builtin_amdgcn_update_dpp(0, dc, 0x4E, 0xf, 0xf, false);     // lanes 2 3 0 1
+    if (kSplitWaves / per == 4) dc += __builtin_amdgcn_update_dpp(0, dc, 0x4E, 0xf, 0xf, false);     // lanes 2 3 0 1
     if (d < nd && w0 == 0) { dstart[d] = ex; dcount[d] = dc; }
     __syncthreads();
 }
 
-__device__ __forceinline__ int split_rank(int* cnt_row, unsigned m) {
-    const unsigned tot = m & 0xFFu, before = (m >> 8) & 0x3Fu;
-    int r = 0;
-    if (tot) r = cnt_row[m >> 16];
-    if (tot && before == 0) cnt_row[m >> 16] = r + (int)tot;     // same wavefront, after the group's reads
-    return r + (int)before;
-}
-
 // One tile of <= tile_post postings of one head: split by bucket, write the tile and its piece table.
 // `src` is the first row of tile `tile0` (row stride k, head stride head_stride elements).
-__global__ __launch_bounds__(kSplitThreads, 8) void idx_partition_kernel(const int32_t* src, int64_t head_stride,
+__global__ __launch_bounds__(kSplitThreads, kSplitOcc) void idx_partition_kernel(const int32_t* src, int64_t head_stride,
                                                                          int rows_avail, int tile0, IdxDev d) {
     __shared__ int cnt[kSplitWaves * 256];
     __shared__ uint32_t stage[kTilePost];
@@ -169,28 +170,35 @@ __global__ __launch_bounds__(kSplitThreads, 8) void idx_partition_kernel(const i
     const uint32_t row0 = (uint32_t)tile * (uint32_t)d.ptok;
     const int nd = 1 << d.nbB;
 
-    for (int i = tid; i < kSplitWaves * nd; i += kSplitThreads) cnt[i] = 0;
-    __syncthreads();
     int* row = cnt + wave * nd;
     uint32_t word[kSplitRounds];
-    unsigned meta[kSplitRounds];       // match_lanes() | bucket << 16
+    unsigned meta[kSplitRounds];       // split_round()
+    const int i0 = wave * (kSplitRounds * 64) + lane;
+    if (i0 - lane + kSplitRounds * 64 <= n) {      // uniform: the wavefront's whole share exists
+#pragma unroll
+        for (int r = 0; r < kSplitRounds; ++r) word[r] = (uint32_t)s[i0 + r * 64];
+    } else {                                       // ragged tail: read a clamped index, drop it below
+#pragma unroll
+        for (int r = 0; r < kSplitRounds; ++r) word[r] = (uint32_t)s[min(i0 + r * 64, n - 1)];
+    }
+    for (int i = tid; i < kSplitWaves * nd; i += kSplitThreads) cnt[i] = 0;      // while the loads are in flight
+    __syncthreads();
+    const uint32_t k_is_1 = d.k == 1;
 #pragma unroll
     for (int r = 0; r < kSplitRounds; ++r) {
-        const uint32_t i = (uint32_t)((wave * kSplitRounds + r) * 64 + lane);
+        const uint32_t i = (uint32_t)(i0 + r * 64);
         const bool valid = (int)i < n;
-        const uint32_t id = valid ? (uint32_t)s[i] : 0u;
+        const uint32_t id = valid ? word[r] : 0u;
         const uint32_t dg = min(id >> d.S, (uint32_t)(nd - 1));   // ids are < n_feat by contract; never index past the counters
-        const uint32_t trow = d.k > 1 ? __umulhi(i, d.kinv) : i;
+        const uint32_t trow = __umulhi(i, d.kinv) + i * k_is_1;   // i / k (kinv is 0 when k == 1)
         word[r] = ((row0 + trow) << d.S) | (id & mask);
-        meta[r] = match_lanes<8>(dg, valid) | (dg << 16);
-        split_count(row, meta[r]);
+        meta[r] = split_round<8>(row, dg, valid);
     }
     __syncthreads();
     split_scan(cnt, nd, bstart, bcount, wsum);
 #pragma unroll
     for (int r = 0; r < kSplitRounds; ++r) {
-        const int rk = split_rank(row, meta[r]);
-        if (meta[r] & 0xFFu) stage[rk] = word[r];
+        if (meta[r] & kSplitValid) stage[split_rank(row, meta[r])] = word[r];
     }
     __syncthreads();
     uint32_t* out = d.inter + (size_t)head * d.inter_stride + (size_t)tile * d.tile_post;
@@ -230,7 +238,7 @@ __global__ __launch_bounds__(256) void idx_bucket_scan_kernel(IdxDev d) {
 // staged in LDS and written as one contiguous run.  A larger bucket (a very frequent feature) is counted
 // first and then taken in rounds of whole pieces, each round writing behind per-feature cursors.
 template <int NBITS>
-__global__ __launch_bounds__(kSplitThreads, 8) void idx_bucket_sort_kernel(IdxDev d, int n_tiles) {
+__global__ __launch_bounds__(kSplitThreads, kSplitOcc) void idx_bucket_sort_kernel(IdxDev d, int n_tiles) {
     extern __shared__ __align__(16) uint32_t dyn[];
     uint32_t* bufa = dyn;                          // [kSortCap] gathered entries of the round; once every wavefront
     int32_t* bufb = (int32_t*)dyn;                 // holds its entries in registers: the sorted positions (same memory)
@@ -245,6 +253,9 @@ __global__ __launch_bounds__(kSplitThreads, 8) void idx_bucket_sort_kernel(IdxDe
 
     const int tid = threadIdx.x, lane = tid & 63, b = blockIdx.x, head = blockIdx.y;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    // the first round's piece words are requested together with the bucket's totals: one memory latency, not two
+    const uint32_t* pc = d.piece + (size_t)head * d.piece_stride + (size_t)b * d.max_tiles;
+    uint32_t p_next = tid < n_tiles ? pc[tid] : 0u;
     const int n_b = d.total[(size_t)head * d.NB + b];
     const int out_base = d.bbase[(size_t)head * (d.NB + 1) + b];
     const int nd = 1 << d.S;
@@ -255,7 +266,6 @@ __global__ __launch_bounds__(kSplitThreads, 8) void idx_bucket_sort_kernel(IdxDe
         if (tid < nfl) offs[tid] = out_base;
         return;
     }
-    const uint32_t* pc = d.piece + (size_t)head * d.piece_stride + (size_t)b * d.max_tiles;
     const uint32_t* inter = d.inter + (size_t)head * d.inter_stride;
     int32_t* posout = d.positions + (size_t)head * d.pos_stride;
     const bool multi = n_b > kSortCap || n_tiles > kSplitThreads;   // more than one round of pieces
@@ -279,8 +289,7 @@ __global__ __launch_bounds__(kSplitThreads, 8) void idx_bucket_sort_kernel(IdxDe
 
     for (int tp = 0; tp < n_tiles;) {
         // take as many whole pieces (in tile order) as fit in one round; thread t looks at piece tp + t
-        const int t = tp + tid;
-        const uint32_t p = t < n_tiles ? pc[t] : 0u;
+        const uint32_t p = p_next;
         const int c = (int)(p & 0xFFFFu);
         int tot;
         const int ex = block_excl_scan<kSplitThreads>(c, wsum, tot);
@@ -290,13 +299,13 @@ __global__ __launch_bounds__(kSplitThreads, 8) void idx_bucket_sort_kernel(IdxDe
         int m = __syncthreads_count(ex + c <= kSortCap);    // prefix property: the first m threads qualify
         m = min(m, n_tiles - tp);
         const int n_r = pref[m];
-        // gather: a half wavefront copies one piece; four pieces per step so that four loads are in flight
+        // gather: a half wavefront copies one piece, four pieces per step
         {
             const int hw = tid >> 5, l0 = tid & 31;
             for (int j0 = hw; j0 < m; j0 += 4 * (kSplitThreads / 32)) {
                 const uint32_t* sp[4];
                 int dst[4], cc[4];
-                uint32_t v[4];
+                uint32_t v[4], v2[4];
 #pragma unroll
                 for (int q = 0; q < 4; ++q) {
                     const int j = j0 + q * (kSplitThreads / 32);
@@ -306,48 +315,57 @@ __global__ __launch_bounds__(kSplitThreads, 8) void idx_bucket_sort_kernel(IdxDe
                     sp[q] = inter + (size_t)(tp + (j < m ? j : 0)) * d.tile_post + (pj >> 16);
                 }
 #pragma unroll
-                for (int q = 0; q < 4; ++q) v[q] = l0 < cc[q] ? sp[q][l0] : 0u;
+                for (int q = 0; q < 4; ++q) {      // the first 64 entries of each piece: eight loads in flight
+                    v[q] = l0 < cc[q] ? sp[q][l0] : 0u;
+                    v2[q] = l0 + 32 < cc[q] ? sp[q][l0 + 32] : 0u;
+                }
 #pragma unroll
-                for (int q = 0; q < 4; ++q)
+                for (int q = 0; q < 4; ++q) {
                     if (l0 < cc[q]) bufa[dst[q] + l0] = v[q];
+                    if (l0 + 32 < cc[q]) bufa[dst[q] + l0 + 32] = v2[q];
+                }
 #pragma unroll
                 for (int q = 0; q < 4; ++q)
-                    for (int l = l0 + 32; l < cc[q]; l += 32) bufa[dst[q] + l] = sp[q][l];
+                    for (int l = l0 + 64; l < cc[q]; l += 32) bufa[dst[q] + l] = sp[q][l];
             }
         }
         for (int i = tid; i < kSplitWaves * nd; i += kSplitThreads) cnt[i] = 0;
         __syncthreads();
 
         int* row = cnt + wave * nd;
-        const int seg = ((n_r + kSplitWaves - 1) / kSplitWaves + 63) & ~63;      // entries per wavefront (<= 512)
+        const int seg = ((n_r + kSplitWaves - 1) / kSplitWaves + 63) & ~63;      // entries per wavefront (<= 64 kSplitRounds)
         int32_t pos[kSplitRounds];
-        unsigned meta[kSplitRounds];       // match_lanes() | low feature bits << 16
+        unsigned meta[kSplitRounds];       // split_round()
+#pragma unroll
+        for (int r = 0; r < kSplitRounds; ++r) {
+            const int i = wave * seg + r * 64 + lane;
+            const uint32_t e = (r * 64 < seg && i < n_r) ? bufa[i] : 0u;
+            meta[r] = e;
+            pos[r] = d.pos_log[e >> d.S];      // all loads in flight at once; used only after the scan (row 0 if idle)
+        }
 #pragma unroll
         for (int r = 0; r < kSplitRounds; ++r) {
             if (r * 64 >= seg) {          // uniform: this round is past the wavefront's share
-                pos[r] = 0;
                 meta[r] = 0u;
                 continue;
             }
-            const int i = wave * seg + r * 64 + lane;
-            const bool valid = i < n_r;
-            const uint32_t e = valid ? bufa[i] : 0u;
-            pos[r] = valid ? d.pos_log[e >> d.S] : 0;       // needed only after the scan: the load has time to land
-            meta[r] = match_lanes<NBITS>(e & mask, valid) | ((e & mask) << 16);
-            split_count(row, meta[r]);
+            const bool valid = wave * seg + r * 64 + lane < n_r;
+            meta[r] = split_round<NBITS>(row, meta[r] & mask, valid);
         }
         __syncthreads();
         split_scan(cnt, nd, rstart, rcount, wsum);
         if (!multi && tid < nfl) offs[tid] = out_base + rstart[tid];
+        if (multi) {
 #pragma unroll
-        for (int r = 0; r < kSplitRounds; ++r) {
-            if (r * 64 >= seg) continue;
-            const int rk = split_rank(row, meta[r]);
-            if (meta[r] & 0xFFu) {
-                const unsigned fl = meta[r] >> 16;
-                if (multi) posout[cursor[fl] + (rk - rstart[fl])] = pos[r];
-                else bufb[rk] = pos[r];
-            }
+            for (int r = 0; r < kSplitRounds; ++r)
+                if (meta[r] & kSplitValid) {
+                    const unsigned fl = meta[r] & 0xFFu;
+                    posout[cursor[fl] + (split_rank(row, meta[r]) - rstart[fl])] = pos[r];
+                }
+        } else {
+#pragma unroll
+            for (int r = 0; r < kSplitRounds; ++r)
+                if (meta[r] & kSplitValid) bufb[split_rank(row, meta[r])] = pos[r];
         }
         __syncthreads();
         if (multi) {
@@ -356,6 +374,7 @@ __global__ __launch_bounds__(kSplitThreads, 8) void idx_bucket_sort_kernel(IdxDe
             for (int i = tid; i < n_r; i += kSplitThreads) posout[out_base + i] = bufb[i];
         }
         tp += m;
+        if (tp < n_tiles) p_next = tp + tid < n_tiles ? pc[tp + tid] : 0u;
         __syncthreads();
     }
 }
