@@ -24,6 +24,12 @@ struct Scal {
     unsigned long long qwmax_bits;   // bits (as double) of the largest query weight
 };
 
+// A posting list with a non-zero query weight: CSR bounds and the weight.
+struct ActiveList {
+    double w;
+    int32_t b, e;
+};
+
 struct ScoreArgs {
     const int32_t* qids;
     const float* qvals;
@@ -36,6 +42,8 @@ struct ScoreArgs {
     int32_t max_freq;
     Scal* sc;
     unsigned long long* qacc;        // [n_heads * n_feat] fixed-point sums, then doubles (query weights)
+    ActiveList* act;                 // [n_heads * n_feat] lists with a non-zero weight, packed per head (LDS scatter)
+    int* nact;                       // [n_heads] their number
     unsigned long long* sfix;        // [L]
     unsigned long long* part;        // [ngroup][L] partial sums of head groups (ngroup > 1)
     int pb, npb, heads_per, ngroup, sorted;   // position blocks / head groups of the LDS scatter
@@ -95,23 +103,45 @@ __global__ __launch_bounds__(256) void sc_qacc_kernel(ScoreArgs a) {
     }
 }
 
-// fixed-point sum -> query weight (double, stored in place); App. D.2 IDF with natural log
+// fixed-point sum -> query weight (double, stored in place); App. D.2 IDF with natural log.  For the LDS scatter the
+// lists with a non-zero weight are also packed per head (in any order: the scores are exact integer sums).
 __global__ __launch_bounds__(256) void sc_qw_kernel(ScoreArgs a) {
     const size_t n = (size_t)a.n_heads * a.n_feat;
     const double inv = ldexp(1.0, -exp_q(a.sc));
+    const int lane = threadIdx.x & 63;
     double mx = 0.0;
     for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (size_t)gridDim.x * 256) {
         unsigned long long s = a.qacc[i];
+        const int h = (int)(i / a.n_feat);
         double w = 0.0;
+        int lb = 0, le = 0;
         if (s) {
-            size_t h = i / a.n_feat, f = i - h * a.n_feat;
-            const int32_t* off = a.offsets + h * a.off_stride;
-            int freq = off[f + 1] - off[f];
+            const size_t f = i - (size_t)h * a.n_feat;
+            const int32_t* off = a.offsets + (size_t)h * a.off_stride;
+            lb = off[f];
+            le = off[f + 1];
+            const int freq = le - lb;
             if (freq > 0 && !(a.max_freq > 0 && freq > a.max_freq))
                 w = (double)s * inv / (log(1.0 + (double)freq) + 1.0);
         }
         a.qacc[i] = (unsigned long long)__double_as_longlong(w);
         mx = fmax(mx, w);
+        const bool actv = a.npb && w > 0.0;
+        const unsigned long long am = __ballot(actv);
+        if (am) {
+            // one counter update per wavefront when its lanes are in one head (always, but at a head boundary)
+            const int h0 = __builtin_amdgcn_readfirstlane(h);
+            int slot = 0;
+            if (__all(h == h0)) {
+                const int leader = (int)__builtin_ctzll(am);
+                int base = 0;
+                if (lane == leader) base = atomicAdd(&a.nact[h0], (int)__popcll(am));
+                slot = __shfl(base, leader) + (int)__popcll(am & ((1ull << lane) - 1ull));
+            } else if (actv) {
+                slot = atomicAdd(&a.nact[h], 1);
+            }
+            if (actv) a.act[(size_t)h * a.n_feat + slot] = ActiveList{w, lb, le};
+        }
     }
     unsigned long long mb = (unsigned long long)__double_as_longlong(mx);
 #pragma unroll
@@ -147,8 +177,9 @@ __global__ __launch_bounds__(256) void sc_scatter_kernel(ScoreArgs a) {
 // of those heads that has a non-zero weight and adds the postings that fall into its block with LDS atomics
 // (64-bit fixed point, so the order of the additions does not matter), then stores the block: into S when there
 // is one head group, else into that group's partial array (summed by sc_reduce_kernel).  No global atomics.
-// A wavefront takes 64 features at a time: lane l fetches weight and list bounds of feature l, then the lists
-// are walked four at a time (lanes over postings) so that four independent loads are in flight.
+// The lists with a non-zero weight were packed per head by sc_qw_kernel.  A wavefront takes 64 of them at a time:
+// lane l fetches weight and bounds of list l, then the lists are walked four at a time (lanes over postings) so
+// that four independent loads are in flight.
 // Lists are sorted by position when the index was fed increasing implicit positions; long lists are then
 // narrowed to the block by a per-lane binary search first.
 constexpr int kScatterThreads = 1024;
@@ -174,19 +205,18 @@ __global__ __launch_bounds__(kScatterThreads) void sc_scatter_lds_kernel(ScoreAr
     const double scale = ldexp(1.0, exp_s(a.sc, a.hb));
     const int h0 = blockIdx.y * a.heads_per, h1 = min(a.n_heads, h0 + a.heads_per);
     for (int h = h0; h < h1; ++h) {
-        const int32_t* off = a.offsets + (size_t)h * a.off_stride;
         const int32_t* pos = a.positions + (size_t)h * a.pos_stride;
-        const unsigned long long* qw = a.qacc + (size_t)h * a.n_feat;
-        for (int f0 = wave * 64; f0 < a.n_feat; f0 += (kScatterThreads / 64) * 64) {
-            const int f = f0 + lane;
+        const ActiveList* act = a.act + (size_t)h * a.n_feat;
+        const int n_act = a.nact[h];
+        for (int i0 = wave * 64; i0 < n_act; i0 += (kScatterThreads / 64) * 64) {
             unsigned long long wf = 0;
             int b = 0, e = 0;
-            if (f < a.n_feat) {
-                const double w = __longlong_as_double((long long)qw[f]);
-                if (w > 0.0) wf = (unsigned long long)llrint(w * scale);
+            if (i0 + lane < n_act) {
+                const ActiveList l = act[i0 + lane];
+                wf = (unsigned long long)llrint(l.w * scale);
                 if (wf) {
-                    b = off[f];
-                    e = off[f + 1];
+                    b = l.b;
+                    e = l.e;
                     if (a.sorted && a.npb > 1 && e - b > 128) {
                         b = lower_bound_pos(pos, b, e, p0);
                         e = lower_bound_pos(pos, b, e, p1);
@@ -217,11 +247,16 @@ __global__ __launch_bounds__(kScatterThreads) void sc_scatter_lds_kernel(ScoreAr
                     if (pp[j] >= 0 && r < span) atomicAdd(&sblk[r], ww[j]);
                 }
 #pragma unroll
-                for (int j = 0; j < 4; ++j)     // rest of a long list
-                    for (int q = bb[j] + 64 + lane; q < ee[j]; q += 64) {
-                        const int32_t pq = pos[q];
-                        const unsigned r = (unsigned)((int64_t)pq - p0);
-                        if (pq >= 0 && r < span) atomicAdd(&sblk[r], ww[j]);
+                for (int j = 0; j < 4; ++j)     // rest of a long list, 256 postings (four loads in flight) per step
+                    for (int q0 = bb[j] + 64 + lane; q0 - lane < ee[j]; q0 += 256) {
+                        int32_t pq[4];
+#pragma unroll
+                        for (int u = 0; u < 4; ++u) pq[u] = q0 + u * 64 < ee[j] ? pos[q0 + u * 64] : -1;
+#pragma unroll
+                        for (int u = 0; u < 4; ++u) {
+                            const unsigned r = (unsigned)((int64_t)pq[u] - p0);
+                            if (pq[u] >= 0 && r < span) atomicAdd(&sblk[r], ww[j]);
+                        }
                     }
             }
         }
@@ -333,7 +368,7 @@ __global__ __launch_bounds__(kTileW) void sc_topb_kernel(ScoreArgs a) {
 }
 
 struct Layout {
-    size_t sc, qacc, sfix, wfix, dead, tmaxv, tmaxi, part, total;
+    size_t sc, qacc, nact, sfix, wfix, dead, tmaxv, tmaxi, part, act, total;
     int pb, npb, heads_per, ngroup;   // LDS scatter geometry (npb == 0: the global-atomic scatter is used)
 };
 
@@ -345,21 +380,23 @@ Layout layout(int n_heads, int n_feat, int64_t L) {
     l.sc = take(sizeof(Scal));
     l.sfix = take((size_t)L * 8);            // sc and sfix are adjacent: zeroed together with qacc
     l.qacc = take((size_t)n_heads * n_feat * 8);
+    l.nact = take((size_t)n_heads * 4);     // zeroed with the three before it
     l.wfix = take((size_t)L * 8);
     l.dead = take((size_t)L);
     l.tmaxv = take(ntile * 8);
     l.tmaxi = take(ntile * 4);
-    // position blocks of at most kMaxPB scores (128 KB of LDS); enough head groups for about 512 workgroups
+    // position blocks of at most kMaxPB scores (128 KB of LDS); enough head groups for about one workgroup per compute unit
     l.pb = (int)(L < kMaxPB ? (L + 63) / 64 * 64 : kMaxPB);
     const int64_t npb = (L + l.pb - 1) / l.pb;
     l.npb = npb <= 8 ? (int)npb : 0;
-    l.heads_per = 1; l.ngroup = 1; l.part = o;
+    l.heads_per = 1; l.ngroup = 1; l.part = o; l.act = o;
     if (l.npb) {
-        int want = 512 / l.npb;
+        int want = 256 / l.npb;
         int groups = n_heads < want ? n_heads : (want < 1 ? 1 : want);
         l.heads_per = (n_heads + groups - 1) / groups;
         l.ngroup = (n_heads + l.heads_per - 1) / l.heads_per;
         if (l.ngroup > 1) l.part = take((size_t)l.ngroup * L * 8);
+        l.act = take((size_t)n_heads * n_feat * sizeof(ActiveList));
     }
     l.total = o;
     return l;
@@ -409,6 +446,8 @@ extern "C" int s3_coactivate_score(const s3_index* idx, const int32_t* qids, con
     a.sc = (Scal*)(base + l.sc);
     a.sfix = (unsigned long long*)(base + l.sfix);
     a.qacc = (unsigned long long*)(base + l.qacc);
+    a.nact = (int*)(base + l.nact);
+    a.act = (ActiveList*)(base + l.act);
     a.wfix = (long long*)(base + l.wfix);
     a.dead = (unsigned char*)(base + l.dead);
     a.tmaxv = (long long*)(base + l.tmaxv);
@@ -419,7 +458,7 @@ extern "C" int s3_coactivate_score(const s3_index* idx, const int32_t* qids, con
     a.scores_out = scores_out; a.span_start = span_start; a.span_score = span_score; a.n_found = n_found;
 
     hipStream_t st = (hipStream_t)stream;
-    const size_t nzero = (l.wfix - l.sc) / 8;   // Scal + sfix + qacc
+    const size_t nzero = (l.wfix - l.sc) / 8;   // Scal + sfix + qacc + nact
     auto blocks = [](size_t n, size_t per) { size_t b = (n + per - 1) / per; return (unsigned)(b < 1 ? 1 : (b > 65536 ? 65536 : b)); };
     hipLaunchKernelGGL(sc_zero_kernel, dim3(blocks(nzero, 256)), dim3(256), 0, st, (unsigned long long*)(base + l.sc), nzero);
     const size_t npairs = (size_t)a.n_heads * nq * a.k;
