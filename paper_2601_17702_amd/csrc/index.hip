@@ -42,39 +42,6 @@ struct IdxDev {
     uint32_t kinv;        // ceil(2^32 / k) for k > 1: i / k == umulhi(i, kinv) for every posting index of a tile
 };
 
-// Inclusive prefix sums over the lanes of a wavefront / over each row of 16 lanes, by data-parallel-primitive
-// lane shifts: row_shr 1, 2, 4, 8 inside the rows, then lane 15 of a row into the next row, lane 31 into rows 2, 3.
-__device__ __forceinline__ int row_incl_scan(int x) {
-    x += __builtin_amdgcn_update_dpp(0, x, 0x111, 0xf, 0xf, false);
-    x += __builtin_amdgcn_update_dpp(0, x, 0x112, 0xf, 0xf, false);
-    x += __builtin_amdgcn_update_dpp(0, x, 0x114, 0xf, 0xf, false);
-    x += __builtin_amdgcn_update_dpp(0, x, 0x118, 0xf, 0xf, false);
-    return x;
-}
-__device__ __forceinline__ int wave_incl_scan(int x) {
-    x = row_incl_scan(x);
-    x += __builtin_amdgcn_update_dpp(0, x, 0x142, 0xa, 0xf, false);
-    x += __builtin_amdgcn_update_dpp(0, x, 0x143, 0xc, 0xf, false);
-    return x;
-}
-
-// Exclusive prefix sum of one int per thread over the block, in thread order.  wsum: one int per wavefront.
-template <int NT>
-__device__ __forceinline__ int block_excl_scan(int v, int* wsum, int& total) {
-    constexpr int NW = NT / 64;
-    static_assert(NW == 4 || NW == 8 || NW == 16, "wavefront sums are scanned inside one row of 16 lanes");
-    const int lane = threadIdx.x & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int x = wave_incl_scan(v);
-    if (lane == 63) wsum[wave] = x;
-    __syncthreads();
-    const int s = row_incl_scan(wsum[lane & (NW - 1)]);     // lanes 0 .. NW-1: sums of wavefronts 0 .. lane
-    __syncthreads();
-    total = __builtin_amdgcn_readlane(s, NW - 1);
-    const int base = wave ? __builtin_amdgcn_readlane(s, wave - 1) : 0;
-    return base + x - v;
-}
-
 // Stable multi-way split of up to kSplitWaves * kSplitRounds * 64 keyed entries by a digit of at most 8 bits.
 // Wavefront w owns the entries [w seg, (w + 1) seg) in rounds of 64 (lane order = entry order).
 //   count   : split_round() per round: the lanes that share a digit find each other with one ballot per digit bit;
@@ -133,7 +100,7 @@ __device__ __forceinline__ void split_scan(int* cnt, int nd, int* dstart, int* d
         s += v[j];
     }
     int tot;
-    int ex = block_excl_scan<kSplitThreads>(s, wsum, tot);
+    int ex = s3_block_excl_scan<kSplitThreads>(s, wsum, tot);
     if (d < nd) {
         int run = ex;
 #pragma unroll
@@ -215,7 +182,7 @@ __global__ __launch_bounds__(256) void idx_totals_kernel(IdxDev d, int n_tiles) 
     int acc = 0;
     for (int t = threadIdx.x; t < n_tiles; t += 256) acc += (int)(pc[t] & 0xFFFFu);
     int tot;
-    block_excl_scan<256>(acc, wsum, tot);
+    s3_block_excl_scan<256>(acc, wsum, tot);
     if (threadIdx.x == 0) d.total[(size_t)head * d.NB + b] = tot;
 }
 
@@ -224,7 +191,7 @@ __global__ __launch_bounds__(256) void idx_bucket_scan_kernel(IdxDev d) {
     const int head = blockIdx.x, b = threadIdx.x;
     int v = b < d.NB ? d.total[(size_t)head * d.NB + b] : 0;
     int tot;
-    int ex = block_excl_scan<256>(v, wsum, tot);
+    int ex = s3_block_excl_scan<256>(v, wsum, tot);
     int32_t* bb = d.bbase + (size_t)head * (d.NB + 1);
     if (b < d.NB) bb[b] = ex;
     if (b == 0) {
@@ -281,7 +248,7 @@ __global__ __launch_bounds__(kSplitThreads, kSplitOcc) void idx_bucket_sort_kern
         }
         __syncthreads();
         int tot;
-        int ex = block_excl_scan<kSplitThreads>(tid < nd ? hist[tid] : 0, wsum, tot);
+        int ex = s3_block_excl_scan<kSplitThreads>(tid < nd ? hist[tid] : 0, wsum, tot);
         if (tid < nd) cursor[tid] = out_base + ex;
         if (tid < nfl) offs[tid] = out_base + ex;
         __syncthreads();
@@ -292,7 +259,7 @@ __global__ __launch_bounds__(kSplitThreads, kSplitOcc) void idx_bucket_sort_kern
         const uint32_t p = p_next;
         const int c = (int)(p & 0xFFFFu);
         int tot;
-        const int ex = block_excl_scan<kSplitThreads>(c, wsum, tot);
+        const int ex = s3_block_excl_scan<kSplitThreads>(c, wsum, tot);
         pref[tid] = ex;
         pinfo[tid] = p;
         if (tid == kSplitThreads - 1) pref[kSplitThreads] = tot;

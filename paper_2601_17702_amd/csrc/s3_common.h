@@ -27,6 +27,40 @@ void s3_index_view(const s3_index* idx, int* n_heads, int* n_feat, int* k, int64
                    const int32_t** offsets, int64_t* off_stride, const int32_t** positions,
                    int64_t* pos_stride, bool* finalized, bool* sorted);
 
+// ---- prefix sums shared by the index and the scoring kernels ----
+// Inclusive prefix sums over the lanes of a wavefront / over each row of 16 lanes, by data-parallel-primitive
+// lane shifts: row_shr 1, 2, 4, 8 inside the rows, then lane 15 of a row into the next row, lane 31 into rows 2, 3.
+__device__ __forceinline__ int s3_row_incl_scan(int x) {
+    x += __builtin_amdgcn_update_dpp(0, x, 0x111, 0xf, 0xf, false);
+    x += __builtin_amdgcn_update_dpp(0, x, 0x112, 0xf, 0xf, false);
+    x += __builtin_amdgcn_update_dpp(0, x, 0x114, 0xf, 0xf, false);
+    x += __builtin_amdgcn_update_dpp(0, x, 0x118, 0xf, 0xf, false);
+    return x;
+}
+__device__ __forceinline__ int s3_wave_incl_scan(int x) {
+    x = s3_row_incl_scan(x);
+    x += __builtin_amdgcn_update_dpp(0, x, 0x142, 0xa, 0xf, false);
+    x += __builtin_amdgcn_update_dpp(0, x, 0x143, 0xc, 0xf, false);
+    return x;
+}
+
+// Exclusive prefix sum of one int per thread over the block, in thread order.  wsum: one int per wavefront.
+template <int NT>
+__device__ __forceinline__ int s3_block_excl_scan(int v, int* wsum, int& total) {
+    constexpr int NW = NT / 64;
+    static_assert(NW == 4 || NW == 8 || NW == 16, "wavefront sums are scanned inside one row of 16 lanes");
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int x = s3_wave_incl_scan(v);
+    if (lane == 63) wsum[wave] = x;
+    __syncthreads();
+    const int s = s3_row_incl_scan(wsum[lane & (NW - 1)]);     // lanes 0 .. NW-1: sums of wavefronts 0 .. lane
+    __syncthreads();
+    total = __builtin_amdgcn_readlane(s, NW - 1);
+    const int base = wave ? __builtin_amdgcn_readlane(s, wave - 1) : 0;
+    return base + x - v;
+}
+
 // ---- encoder internals shared by the generic and the fast kernel ----
 struct EncParams {
     const char* x;

@@ -87,7 +87,13 @@ __global__ __launch_bounds__(256) void sc_qmax_kernel(ScoreArgs a) {
         m = max(m, __float_as_uint(fmaxf(a.qvals[i], 0.f)));
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) m = max(m, (unsigned int)__shfl_xor((int)m, o));
-    if ((threadIdx.x & 63) == 0 && m) atomicMax(&a.sc->qmax_bits, m);
+    __shared__ unsigned int wmax[4];     // one atomic per block: they all hit the same word
+    if ((threadIdx.x & 63) == 0) wmax[threadIdx.x >> 6] = m;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        m = max(max(wmax[0], wmax[1]), max(wmax[2], wmax[3]));
+        if (m) atomicMax(&a.sc->qmax_bits, m);
+    }
 }
 
 __global__ __launch_bounds__(256) void sc_qacc_kernel(ScoreArgs a) {
@@ -105,42 +111,63 @@ __global__ __launch_bounds__(256) void sc_qacc_kernel(ScoreArgs a) {
 
 // fixed-point sum -> query weight (double, stored in place); App. D.2 IDF with natural log.  For the LDS scatter the
 // lists with a non-zero weight are also packed per head (in any order: the scores are exact integer sums).
+// A block owns kQwPer * 256 consecutive (head, feature) entries: it packs its lists locally (prefix sum) and
+// reserves their place in the head's array with one atomic, so a head's counter sees few updates.
+constexpr int kQwPer = 16;
+
 __global__ __launch_bounds__(256) void sc_qw_kernel(ScoreArgs a) {
+    __shared__ int wsum[4];
+    __shared__ int slot0;
+    __shared__ unsigned long long wmax[4];
     const size_t n = (size_t)a.n_heads * a.n_feat;
+    const size_t base = (size_t)blockIdx.x * (256 * kQwPer);
+    const size_t end = base + 256 * kQwPer < n ? base + 256 * kQwPer : n;
     const double inv = ldexp(1.0, -exp_q(a.sc));
-    const int lane = threadIdx.x & 63;
+    const int tid = threadIdx.x;
+    double w[kQwPer];
+    int lb[kQwPer], le[kQwPer];
     double mx = 0.0;
-    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (size_t)gridDim.x * 256) {
-        unsigned long long s = a.qacc[i];
-        const int h = (int)(i / a.n_feat);
-        double w = 0.0;
-        int lb = 0, le = 0;
-        if (s) {
-            const size_t f = i - (size_t)h * a.n_feat;
-            const int32_t* off = a.offsets + (size_t)h * a.off_stride;
-            lb = off[f];
-            le = off[f + 1];
-            const int freq = le - lb;
-            if (freq > 0 && !(a.max_freq > 0 && freq > a.max_freq))
-                w = (double)s * inv / (log(1.0 + (double)freq) + 1.0);
-        }
-        a.qacc[i] = (unsigned long long)__double_as_longlong(w);
-        mx = fmax(mx, w);
-        const bool actv = a.npb && w > 0.0;
-        const unsigned long long am = __ballot(actv);
-        if (am) {
-            // one counter update per wavefront when its lanes are in one head (always, but at a head boundary)
-            const int h0 = __builtin_amdgcn_readfirstlane(h);
-            int slot = 0;
-            if (__all(h == h0)) {
-                const int leader = (int)__builtin_ctzll(am);
-                int base = 0;
-                if (lane == leader) base = atomicAdd(&a.nact[h0], (int)__popcll(am));
-                slot = __shfl(base, leader) + (int)__popcll(am & ((1ull << lane) - 1ull));
-            } else if (actv) {
-                slot = atomicAdd(&a.nact[h], 1);
+#pragma unroll
+    for (int j = 0; j < kQwPer; ++j) {
+        const size_t i = base + (size_t)j * 256 + tid;
+        w[j] = 0.0;
+        lb[j] = le[j] = 0;
+        if (i < n) {
+            const unsigned long long s = a.qacc[i];
+            if (s) {
+                const size_t h = i / a.n_feat, f = i - h * a.n_feat;
+                const int32_t* off = a.offsets + h * a.off_stride;
+                lb[j] = off[f];
+                le[j] = off[f + 1];
+                const int freq = le[j] - lb[j];
+                if (freq > 0 && !(a.max_freq > 0 && freq > a.max_freq))
+                    w[j] = (double)s * inv / (log(1.0 + (double)freq) + 1.0);
             }
-            if (actv) a.act[(size_t)h * a.n_feat + slot] = ActiveList{w, lb, le};
+            a.qacc[i] = (unsigned long long)__double_as_longlong(w[j]);
+            mx = fmax(mx, w[j]);
+        }
+    }
+    if (a.npb) {
+        const size_t h_last = (end - 1) / a.n_feat;
+        for (size_t h = base / a.n_feat; h <= h_last; ++h) {      // the heads this block's entries belong to (mostly one)
+            const size_t s0 = h * a.n_feat, s1 = s0 + a.n_feat;
+            int c = 0;
+#pragma unroll
+            for (int j = 0; j < kQwPer; ++j) {
+                const size_t i = base + (size_t)j * 256 + tid;
+                c += (w[j] > 0.0 && i >= s0 && i < s1) ? 1 : 0;
+            }
+            int tot;
+            const int ex = s3_block_excl_scan<256>(c, wsum, tot);
+            if (tid == 0) slot0 = tot ? atomicAdd(&a.nact[h], tot) : 0;
+            __syncthreads();
+            int slot = slot0 + ex;
+#pragma unroll
+            for (int j = 0; j < kQwPer; ++j) {
+                const size_t i = base + (size_t)j * 256 + tid;
+                if (w[j] > 0.0 && i >= s0 && i < s1) a.act[s0 + slot++] = ActiveList{w[j], lb[j], le[j]};
+            }
+            __syncthreads();
         }
     }
     unsigned long long mb = (unsigned long long)__double_as_longlong(mx);
@@ -151,7 +178,12 @@ __global__ __launch_bounds__(256) void sc_qw_kernel(ScoreArgs a) {
         unsigned long long other = ((unsigned long long)hi << 32) | lo;
         mb = other > mb ? other : mb;
     }
-    if ((threadIdx.x & 63) == 0 && mb) atomicMax(&a.sc->qwmax_bits, mb);
+    if ((tid & 63) == 0) wmax[tid >> 6] = mb;       // one atomic per block: they all hit the same word
+    __syncthreads();
+    if (tid == 0) {
+        for (int q = 1; q < 4; ++q) mb = wmax[q] > mb ? wmax[q] : mb;
+        if (mb) atomicMax(&a.sc->qwmax_bits, mb);
+    }
 }
 
 // one wavefront per posting list with a non-zero weight
@@ -463,11 +495,10 @@ extern "C" int s3_coactivate_score(const s3_index* idx, const int32_t* qids, con
     hipLaunchKernelGGL(sc_zero_kernel, dim3(blocks(nzero, 256)), dim3(256), 0, st, (unsigned long long*)(base + l.sc), nzero);
     const size_t npairs = (size_t)a.n_heads * nq * a.k;
     if (npairs) {
-        hipLaunchKernelGGL(sc_qmax_kernel, dim3(blocks(npairs, 256 * 4)), dim3(256), 0, st, a);
+        hipLaunchKernelGGL(sc_qmax_kernel, dim3(blocks(npairs, 256 * 4) > 512 ? 512 : blocks(npairs, 256 * 4)), dim3(256), 0, st, a);
         hipLaunchKernelGGL(sc_qacc_kernel, dim3(blocks(npairs, 256)), dim3(256), 0, st, a);
         const size_t nhf = (size_t)a.n_heads * a.n_feat;
-        // few, long-running blocks: every wavefront ends with one atomic on the same word
-        hipLaunchKernelGGL(sc_qw_kernel, dim3(blocks(nhf, 256 * 16) > 2048 ? 2048 : blocks(nhf, 256 * 16)), dim3(256), 0, st, a);
+        hipLaunchKernelGGL(sc_qw_kernel, dim3((unsigned)((nhf + 256 * kQwPer - 1) / (256 * kQwPer))), dim3(256), 0, st, a);
         if (a.npb) {
             static bool attr_set = false;
             if (!attr_set) {
