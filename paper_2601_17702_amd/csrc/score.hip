@@ -25,7 +25,7 @@ struct Scal {
 };
 
 // A posting list with a non-zero query weight: CSR bounds and the weight.
-struct ActiveList {
+struct alignas(16) ActiveList {
     double w;
     int32_t b, e;
 };
@@ -210,19 +210,38 @@ __global__ __launch_bounds__(256) void sc_scatter_kernel(ScoreArgs a) {
 // (64-bit fixed point, so the order of the additions does not matter), then stores the block: into S when there
 // is one head group, else into that group's partial array (summed by sc_reduce_kernel).  No global atomics.
 // The lists with a non-zero weight were packed per head by sc_qw_kernel.  A wavefront takes 64 of them at a time:
-// lane l fetches weight and bounds of list l, then the lists are walked four at a time (lanes over postings) so
-// that four independent loads are in flight.
+// lane l fetches weight and bounds of list l, then the lists are walked kWalk at a time (lanes over postings) so
+// that kWalk independent loads are in flight.
 // Lists are sorted by position when the index was fed increasing implicit positions; long lists are then
 // narrowed to the block by a per-lane binary search first.
 constexpr int kScatterThreads = 1024;
+constexpr int kWalk = 8;             // posting loads a wavefront keeps in flight
+constexpr int kNarrowMin = 128;      // sorted lists longer than this are narrowed to the position block first
+constexpr int kWalkRounds = 4;       // rounds in which kWalk lists advance together before the long rest is walked alone
 constexpr int kMaxPB = 16384;
 
+// First index in [b, e) whose position is >= key (e if none); pos[b .. e) ascending.  Eight-way search: the seven
+// pivots of a step are independent loads, so a list of n postings costs about log8(n) memory latencies.
 __device__ __forceinline__ int lower_bound_pos(const int32_t* pos, int b, int e, int64_t key) {
-    while (b < e) {
-        int m = b + ((e - b) >> 1);
-        if ((int64_t)pos[m] < key) b = m + 1; else e = m;
+    while (e - b > 8) {
+        const int step = (e - b) >> 3;
+        int32_t v[7];
+#pragma unroll
+        for (int u = 0; u < 7; ++u) v[u] = pos[b + (u + 1) * step];
+        int c = 0;
+#pragma unroll
+        for (int u = 0; u < 7; ++u) c += (int64_t)v[u] < key ? 1 : 0;
+        const int nb = c ? b + c * step + 1 : b;          // everything up to the last pivot below the key is below it
+        if (c < 7) e = b + (c + 1) * step;                // the first pivot at or above the key bounds the answer
+        b = nb;
     }
-    return b;
+    int32_t v[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) v[u] = b + u < e ? pos[b + u] : 0;
+    int c = 0;
+#pragma unroll
+    for (int u = 0; u < 8; ++u) c += (b + u < e && (int64_t)v[u] < key) ? 1 : 0;
+    return b + c;
 }
 
 __global__ __launch_bounds__(kScatterThreads) void sc_scatter_lds_kernel(ScoreArgs a) {
@@ -244,50 +263,60 @@ __global__ __launch_bounds__(kScatterThreads) void sc_scatter_lds_kernel(ScoreAr
             unsigned long long wf = 0;
             int b = 0, e = 0;
             if (i0 + lane < n_act) {
-                const ActiveList l = act[i0 + lane];
-                wf = (unsigned long long)llrint(l.w * scale);
+                const uint4 raw = *reinterpret_cast<const uint4*>(act + i0 + lane);      // weight and bounds in one load
+                const double lw = __longlong_as_double((long long)(((unsigned long long)raw.y << 32) | raw.x));
+                wf = (unsigned long long)llrint(lw * scale);
                 if (wf) {
-                    b = l.b;
-                    e = l.e;
-                    if (a.sorted && a.npb > 1 && e - b > 128) {
-                        b = lower_bound_pos(pos, b, e, p0);
-                        e = lower_bound_pos(pos, b, e, p1);
+                    b = (int)raw.z;
+                    e = (int)raw.w;
+                    if (a.sorted && a.npb > 1 && e - b > kNarrowMin) {      // the first and the last block need one search
+                        if (blockIdx.x > 0) b = lower_bound_pos(pos, b, e, p0);
+                        if ((int)blockIdx.x < a.npb - 1) e = lower_bound_pos(pos, b, e, p1);
                     }
                 }
             }
             unsigned long long m = __ballot(e > b);
             while (m) {
-                int it[4], bb[4], ee[4];
-                unsigned long long ww[4];
+                int bb[kWalk], ee[kWalk];
+                unsigned long long ww[kWalk];
 #pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    it[j] = m ? (int)__builtin_ctzll(m) : -1;
+                for (int j = 0; j < kWalk; ++j) {
+                    const int src = m ? (int)__builtin_ctzll(m) : -1;
                     if (m) m &= m - 1;
-                    const int src = it[j] < 0 ? 0 : it[j];
-                    bb[j] = __builtin_amdgcn_readlane(b, src);
-                    ee[j] = it[j] < 0 ? bb[j] : __builtin_amdgcn_readlane(e, src);
-                    const unsigned lo = __builtin_amdgcn_readlane((unsigned)wf, src);
-                    const unsigned hi = __builtin_amdgcn_readlane((unsigned)(wf >> 32), src);
+                    bb[j] = __builtin_amdgcn_readlane(b, src < 0 ? 0 : src);
+                    ee[j] = src < 0 ? bb[j] : __builtin_amdgcn_readlane(e, src);
+                    const unsigned lo = __builtin_amdgcn_readlane((unsigned)wf, src < 0 ? 0 : src);
+                    const unsigned hi = __builtin_amdgcn_readlane((unsigned)(wf >> 32), src < 0 ? 0 : src);
                     ww[j] = ((unsigned long long)hi << 32) | lo;
                 }
-                int32_t pp[4];
+                // the kWalk lists side by side, 64 postings of each per round, for up to kWalkRounds rounds
+                int longest = 0;
 #pragma unroll
-                for (int j = 0; j < 4; ++j) pp[j] = bb[j] + lane < ee[j] ? pos[bb[j] + lane] : -1;
+                for (int j = 0; j < kWalk; ++j) longest = max(longest, ee[j] - bb[j]);
+                const int rounds = min((longest + 63) >> 6, kWalkRounds);
+                for (int r = 0; r < rounds; ++r) {
+                    int32_t pp[kWalk];
 #pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    const unsigned r = (unsigned)((int64_t)pp[j] - p0);
-                    if (pp[j] >= 0 && r < span) atomicAdd(&sblk[r], ww[j]);
+                    for (int j = 0; j < kWalk; ++j) {
+                        const int q = bb[j] + r * 64 + lane;
+                        pp[j] = q < ee[j] ? pos[q] : -1;
+                    }
+#pragma unroll
+                    for (int j = 0; j < kWalk; ++j) {
+                        const unsigned rr = (unsigned)((int64_t)pp[j] - p0);
+                        if (pp[j] >= 0 && rr < span) atomicAdd(&sblk[rr], ww[j]);
+                    }
                 }
 #pragma unroll
-                for (int j = 0; j < 4; ++j)     // rest of a long list, 256 postings (four loads in flight) per step
-                    for (int q0 = bb[j] + 64 + lane; q0 - lane < ee[j]; q0 += 256) {
-                        int32_t pq[4];
+                for (int j = 0; j < kWalk; ++j)     // rest of a very long list, kWalk loads in flight per step
+                    for (int q0 = bb[j] + 64 * kWalkRounds + lane; q0 - lane < ee[j]; q0 += 64 * kWalk) {
+                        int32_t pq[kWalk];
 #pragma unroll
-                        for (int u = 0; u < 4; ++u) pq[u] = q0 + u * 64 < ee[j] ? pos[q0 + u * 64] : -1;
+                        for (int u = 0; u < kWalk; ++u) pq[u] = q0 + u * 64 < ee[j] ? pos[q0 + u * 64] : -1;
 #pragma unroll
-                        for (int u = 0; u < 4; ++u) {
-                            const unsigned r = (unsigned)((int64_t)pq[u] - p0);
-                            if (pq[u] >= 0 && r < span) atomicAdd(&sblk[r], ww[j]);
+                        for (int u = 0; u < kWalk; ++u) {
+                            const unsigned rr = (unsigned)((int64_t)pq[u] - p0);
+                            if (pq[u] >= 0 && rr < span) atomicAdd(&sblk[rr], ww[j]);
                         }
                     }
             }
