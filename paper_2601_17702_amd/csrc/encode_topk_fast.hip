@@ -48,6 +48,7 @@ constexpr int kStageB = kFT * RB;
 constexpr int kBiasB = 256;      // the 64 fp32 biases of a pair of stages (one wavefront-wide copy)
 constexpr int kGuard = 4;        // appends possible between two fullness checks
 constexpr float kHintMargin = 0.03f;   // streamed calls start 3 % below the carried bound
+constexpr float kPilotMargin = 0.03f;  // bounds taken from the pilot's single tile are lowered by this much more
 constexpr int kOffBias = kRing * kStageB;
 constexpr int kOffVote = kOffBias + (kRing / 2) * kBiasB;
 constexpr int kOffVal = kOffVote + 16;
@@ -118,17 +119,26 @@ __global__ void enc_stream_prep_kernel(int32_t* redo_cnt, unsigned* hint_out, fl
 // threshold better depends on the data (pre-activations dominated by W x scale with |x|, those dominated by the
 // bias do not); using both at once would fail whenever either overshoots.  The one that was tighter on average
 // over this call's tokens is carried, the other one is set to -inf.
-__global__ void enc_stream_post_kernel(const unsigned* hint_out, const float* hint_sum, float* hint, int n_heads) {
+// `boot`: null for the bounds carried out of the call.  Else (after the pilot launch) the bounds the caller carried
+// in: heads that had one keep it for the main launch, the others start from the pilot's tile, lowered by `extra`
+// because the minimum over one tile of tokens is a weaker bound than the minimum over a whole chunk.
+__global__ void enc_stream_post_kernel(const unsigned* hint_out, const float* hint_sum, float* hint, int n_heads,
+                                       const float* boot, float extra) {
     const int h = blockIdx.x * blockDim.x + threadIdx.x;
     if (h >= n_heads) return;
+    if (boot && !(boot[2 * h] == -INFINITY && boot[2 * h + 1] == -INFINITY)) {
+        hint[2 * h] = boot[2 * h];
+        hint[2 * h + 1] = boot[2 * h + 1];
+        return;
+    }
     const float r = hint_out[2 * h] == 0xFFFFFFFFu ? -INFINITY : key_value(hint_out[2 * h]);
     const float a = hint_out[2 * h + 1] == 0xFFFFFFFFu ? -INFINITY : key_value(hint_out[2 * h + 1]);
     const float s_tau = hint_sum[3 * h], s_x = hint_sum[3 * h + 1], s_n = hint_sum[3 * h + 2];
     const float waste_r = r > -INFINITY ? s_tau - r * s_x : INFINITY;
     const float waste_a = a > -INFINITY ? s_tau - a * s_n : INFINITY;
     const bool use_r = waste_r <= waste_a;
-    hint[2 * h] = use_r ? r : -INFINITY;
-    hint[2 * h + 1] = use_r ? -INFINITY : a;
+    hint[2 * h] = use_r ? r - extra * fabsf(r) : -INFINITY;
+    hint[2 * h + 1] = use_r ? -INFINITY : a - extra * fabsf(a);
 }
 
 // One build of the kernel per list geometry: 8 wavefronts x 40 slots per lane for k <= 32, 4 wavefronts x 80 slots
@@ -162,35 +172,47 @@ static int fast_dispatch(EncParams p, hipStream_t st);
 
 int s3_encode_fast_launch(EncParams p, hipStream_t st) {
     p.mode = 0;
-    p.hint_in = nullptr; p.hint_out = nullptr; p.hint_sum = nullptr; p.redo_list = nullptr; p.redo_cnt = nullptr;
+    p.hint_in = nullptr; p.boot_in = nullptr; p.hint_out = nullptr; p.hint_sum = nullptr; p.redo_list = nullptr; p.redo_cnt = nullptr;
     return fast_dispatch(p, st);
 }
 
 size_t s3_encode_fast_stream_workspace(int n_heads, int T) {
-    return s3_align((size_t)n_heads * 4) + s3_align((size_t)n_heads * 8) + s3_align((size_t)n_heads * 12) +
+    return s3_align((size_t)n_heads * 4) + 2 * s3_align((size_t)n_heads * 8) + s3_align((size_t)n_heads * 12) +
            s3_align((size_t)n_heads * T * 4);
 }
 
-// Main pass from the carried bounds, redo pass (from -inf) for the tokens whose bound was too high, then this
-// call's minima become the bounds for the next call.  All on `st`; nothing is read back.
+// Pilot (heads without a carried bound: their first token tile, from -inf), main pass from the carried or the
+// pilot's bounds, redo pass (from -inf) for the tokens whose bound was too high; then this call's minima become
+// the bounds for the next call.  All on `st`; nothing is read back.
 int s3_encode_fast_stream(EncParams p, float* hint, void* ws, hipStream_t st) {
     char* base = (char*)ws;
-    p.redo_cnt = (int32_t*)base;
-    p.hint_out = (unsigned*)(base + s3_align((size_t)p.n_heads * 4));
-    p.hint_sum = (float*)(base + s3_align((size_t)p.n_heads * 4) + s3_align((size_t)p.n_heads * 8));
-    p.redo_list = (int32_t*)(base + s3_align((size_t)p.n_heads * 4) + s3_align((size_t)p.n_heads * 8) +
-                             s3_align((size_t)p.n_heads * 12));
-    p.hint_in = hint;
+    size_t o = 0;
+    auto take = [&](size_t bytes) { char* at = base + o; o += s3_align(bytes); return at; };
+    p.redo_cnt = (int32_t*)take((size_t)p.n_heads * 4);
+    p.hint_out = (unsigned*)take((size_t)p.n_heads * 8);
+    float* hint_mid = (float*)take((size_t)p.n_heads * 8);
+    p.hint_sum = (float*)take((size_t)p.n_heads * 12);
+    p.redo_list = (int32_t*)take((size_t)p.n_heads * p.T * 4);
     const int nb = (3 * p.n_heads + 255) / 256;
     hipLaunchKernelGGL(enc_stream_prep_kernel, dim3(nb), dim3(256), 0, st, p.redo_cnt, p.hint_out, p.hint_sum, p.n_heads);
     p.margin = (float)env_int("S3_ENC_MARGIN", (int)(kHintMargin * 1000.f + 0.5f)) * 1e-3f;   // per mille, tuning
-    p.mode = 1;
+    const float extra = (float)env_int("S3_ENC_PILOT_MARGIN", (int)(kPilotMargin * 1000.f + 0.5f)) * 1e-3f;
+    p.boot_in = hint;
+    p.hint_in = nullptr;
+    p.mode = 3;
     int rc = fast_dispatch(p, st);
+    if (rc) return rc;
+    hipLaunchKernelGGL(enc_stream_post_kernel, dim3(nb), dim3(256), 0, st, p.hint_out, p.hint_sum, hint_mid, p.n_heads,
+                       (const float*)hint, extra);
+    p.hint_in = hint_mid;
+    p.mode = 1;
+    rc = fast_dispatch(p, st);
     if (rc) return rc;
     p.mode = 2;
     rc = fast_dispatch(p, st);
     if (rc) return rc;
-    hipLaunchKernelGGL(enc_stream_post_kernel, dim3(nb), dim3(256), 0, st, p.hint_out, p.hint_sum, hint, p.n_heads);
+    hipLaunchKernelGGL(enc_stream_post_kernel, dim3(nb), dim3(256), 0, st, p.hint_out, p.hint_sum, hint, p.n_heads,
+                       (const float*)nullptr, 0.f);
     S3_HIP(hipGetLastError());
     return S3_OK;
 }

@@ -72,8 +72,10 @@ struct EncParams {
     int soft;      // fast path: list length per lane that asks for a workgroup-wide refresh (0: off)
     // streamed calls (threshold carried from the previous chunk), fast path only
     float margin;              // relative margin below the carried bound
-    int mode;                  // 0 plain, 1 start from the carried bound, 2 redo the tokens listed in redo_list
+    int mode;                  // 0 plain, 1 start from the carried bound, 2 redo the tokens listed in redo_list,
+                               // 3 pilot: first token tile of the heads that carry no bound yet, from -inf
     const float* hint_in;      // [n_heads][2]: lower bounds of tau / |x| and of tau seen in the previous call
+    const float* boot_in;      // [n_heads][2]: the bounds the caller carried in (both -inf: the pilot covers tile 0)
     unsigned* hint_out;        // [n_heads][2]: ordered keys of this call's minima (atomicMin)
     float* hint_sum;           // [n_heads][3]: sums of tau, |x| and the token count over this call
     int32_t* redo_list;        // [n_heads][T] tokens whose carried bound was too high
