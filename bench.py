@@ -25,8 +25,8 @@ MFMA_PEAK_TFLOPS = {"bf16": 2500.0, "fp32": 157.3}   # MI355X dense matrix peaks
 HBM_PEAK_GBS = 8000.0
 # HBM bytes per launch of the encoder kernel from the rocprofv3 FETCH_SIZE / WRITE_SIZE runs summarised in
 # profiles/bench_c2_llama8b_hbm_traffic.txt (counter runs cannot be made from inside this script)
-# one chunk call = main pass + redo pass + the pilot's share (one working pilot launch and 15 empty ones per 16-chunk stream)
-MEASURED_TRAFFIC = {"c2_llama8b": 1374608865 + 626749 + (1131876654 + 15 * 67574) // 16}
+# one chunk call = main pass + redo kernel + the pilot's share (one working pilot launch and 15 empty ones per 16-chunk stream)
+MEASURED_TRAFFIC = {"c2_llama8b": 1374670777 + 580531 + (1131817005 + 15 * 75764) // 16}
 
 
 def gen_inputs(w, torch, threads=16):
