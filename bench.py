@@ -194,7 +194,7 @@ def main():
         "stages_ms": {"encode_topk": float(np.sum(enc_ms)) / args.steps, "index_append": float(np.sum(app_ms)) / args.steps,
                       "index_finalize": float(np.mean(fin_ms)), "query_encode": float(np.mean(qenc_ms)),
                       "coactivate_score": float(np.mean(score_ms))},
-        "roofline": {"kernel": "k32::sae_encode_topk_fast_kernel<0>", "bound": "mfma", "achieved": achieved, "peak": peak,
+        "roofline": {"kernel": ("k32" if w.k <= 32 else "k64") + "::sae_encode_topk_fast_kernel<0>", "bound": "mfma", "achieved": achieved, "peak": peak,
                      "unit": "TFLOP/s", "frac": achieved / peak, "traffic": MEASURED_TRAFFIC.get(w.name),
                      "launch_ms": enc_avg, "flop_per_launch": flop_per_launch},
         "stage_rooflines": {
