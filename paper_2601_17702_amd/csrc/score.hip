@@ -3,7 +3,7 @@
 //
 //   1. query weights   qw[h][f] = IDF_h(f) * sum of the query activations that name f
 //   2. postings gather S[t] += qw[h][f] for every t in I_h[f], all heads into one S (per block of positions
-//      in LDS; global atomics only for contexts longer than 8 blocks)
+//      in LDS; global atomics only for contexts longer than 64 blocks = 1 Mi positions)
 //   3. span pooling    W[s] = S[s] + ... + S[s + len - 1]
 //   4. Top-B           greedy best window, optional suppression of overlapping windows
 //
@@ -213,12 +213,13 @@ __global__ __launch_bounds__(256) void sc_scatter_kernel(ScoreArgs a) {
 // lane l fetches weight and bounds of list l, then the lists are walked kWalk at a time (lanes over postings) so
 // that kWalk independent loads are in flight.
 // Lists are sorted by position when the index was fed increasing implicit positions; long lists are then
-// narrowed to the block by a per-lane binary search first.
+// narrowed to the block by a per-lane search first (lower_bound_pos).
 constexpr int kScatterThreads = 1024;
 constexpr int kWalk = 8;             // posting loads a wavefront keeps in flight
 constexpr int kNarrowMin = 128;      // sorted lists longer than this are narrowed to the position block first
 constexpr int kWalkRounds = 4;       // rounds in which kWalk lists advance together before the long rest is walked alone
 constexpr int kMaxPB = 16384;
+constexpr int kMaxBlocks = 64;       // longer contexts (> 1 Mi positions) use the global-atomic scatter
 
 // First index in [b, e) whose position is >= key (e if none); pos[b .. e) ascending.  Eight-way search: the seven
 // pivots of a step are independent loads, so a list of n postings costs about log8(n) memory latencies.
@@ -449,7 +450,7 @@ Layout layout(int n_heads, int n_feat, int64_t L) {
     // position blocks of at most kMaxPB scores (128 KB of LDS); enough head groups for about one workgroup per compute unit
     l.pb = (int)(L < kMaxPB ? (L + 63) / 64 * 64 : kMaxPB);
     const int64_t npb = (L + l.pb - 1) / l.pb;
-    l.npb = npb <= 8 ? (int)npb : 0;
+    l.npb = npb <= kMaxBlocks ? (int)npb : 0;
     l.heads_per = 1; l.ngroup = 1; l.part = o; l.act = o;
     if (l.npb) {
         int want = 256 / l.npb;

@@ -285,3 +285,23 @@ def test_scatter_position_blocks_long_lists_sorted_and_unsorted():
     ix2 = gpu_index(ids, n_feat, positions=perm, chunks=[4096] * 10)
     S2, W2, st2, sc2 = oracle_score(ids, qids, qvals, n_feat, T, 64, 8, 0, True, positions=perm)
     check_score(run_gpu_score(ix2, qids, qvals, T, 64, 8, 0, True), S2, W2, st2, sc2, 64, True)
+
+
+def strided_ids(rng, T, k, n_feat):
+    """Distinct ids per row without a Python loop over rows (rows of 10^6 tokens)."""
+    stride = n_feat // k
+    return ((rng.integers(0, n_feat, T)[:, None] + np.arange(k)[None, :] * stride) % n_feat).astype(np.int32)
+
+
+@pytest.mark.parametrize("T", [150_000, 64 * 16384 + 5000])
+def test_scoring_of_long_contexts(T):
+    """Ten position blocks (LDS gather, every list narrowed by search) and a context beyond 64 blocks, which takes
+    the global-atomic scatter."""
+    rng = np.random.default_rng(T)
+    H, k, n_feat, nq = 2, 2, 64, 4
+    ids = np.stack([strided_ids(rng, T, k, n_feat) for _ in range(H)])
+    qids = np.stack([strided_ids(rng, nq, k, n_feat) for _ in range(H)])
+    qvals = rng.random((H, nq, k)).astype(np.float32)
+    ix = gpu_index(ids, n_feat, chunks=[50_000] * (T // 50_000 + 1))
+    S, W, st_o, sc_o = oracle_score(ids, qids, qvals, n_feat, T, 128, 16, 0, True)
+    check_score(run_gpu_score(ix, qids, qvals, T, 128, 16, 0, True), S, W, st_o, sc_o, 128, True)
