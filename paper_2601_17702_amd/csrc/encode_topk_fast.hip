@@ -147,19 +147,23 @@ namespace k32 {
 #define S3_CFG_WAVES 8
 #define S3_CFG_CAPL 40
 #define S3_CFG_KMAX 32
+#define S3_CFG_ASYNC_B 1      // second-stage fragment reads stay in flight during the epilogue (registers to spare)
 #include "encode_topk_fast_impl.inc"
 #undef S3_CFG_WAVES
 #undef S3_CFG_CAPL
 #undef S3_CFG_KMAX
+#undef S3_CFG_ASYNC_B
 }  // namespace k32
 namespace k64 {
 #define S3_CFG_WAVES 4
 #define S3_CFG_CAPL 80
 #define S3_CFG_KMAX 64
+#define S3_CFG_ASYNC_B 0      // 80-slot register arrays of the refresh leave no registers that are safe from spills
 #include "encode_topk_fast_impl.inc"
 #undef S3_CFG_WAVES
 #undef S3_CFG_CAPL
 #undef S3_CFG_KMAX
+#undef S3_CFG_ASYNC_B
 }  // namespace k64
 
 }  // namespace
