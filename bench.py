@@ -26,7 +26,7 @@ HBM_PEAK_GBS = 8000.0
 # HBM bytes per launch of the encoder kernel from the rocprofv3 FETCH_SIZE / WRITE_SIZE runs summarised in
 # profiles/bench_c2_llama8b_hbm_traffic.txt (counter runs cannot be made from inside this script)
 # one chunk call = main pass + redo kernel + the pilot's share (one working pilot launch and 15 empty ones per 16-chunk stream)
-MEASURED_TRAFFIC = {"c2_llama8b": 1374670777 + 580531 + (1131817005 + 15 * 75764) // 16}
+MEASURED_TRAFFIC = {"c2_llama8b": 1374462359 + 592913 + (1131829718 + 15 * 67572) // 16}
 
 
 def gen_inputs(w, torch, threads=16):

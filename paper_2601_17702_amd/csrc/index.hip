@@ -266,28 +266,25 @@ __global__ __launch_bounds__(kSplitThreads, kSplitOcc) void idx_bucket_sort_kern
         int m = __syncthreads_count(ex + c <= kSortCap);    // prefix property: the first m threads qualify
         m = min(m, n_tiles - tp);
         const int n_r = pref[m];
-        // gather: a half wavefront copies one piece, four pieces per step.  Loads are unconditional (a lane past the
-        // end of its piece re-reads the piece's last entry, a half wavefront without a piece reads entry 0): no
-        // branches, eight loads in flight.  Entry offsets fit 32 bits (max_tokens * k < 2^31).
+        // gather: a half wavefront copies one piece, four pieces per step
         {
             const int hw = tid >> 5, l0 = tid & 31;
             for (int j0 = hw; j0 < m; j0 += 4 * (kSplitThreads / 32)) {
-                uint32_t eo[4], v[4], v2[4];
+                const uint32_t* sp[4];
                 int dst[4], cc[4];
+                uint32_t v[4], v2[4];
 #pragma unroll
                 for (int q = 0; q < 4; ++q) {
-                    const int j = j0 + q * (kSplitThreads / 32);      // < kSplitThreads: pinfo / pref hold an entry
-                    const bool ok = j < m;
-                    const uint32_t pj = ok ? pinfo[j] : 0u;
+                    const int j = j0 + q * (kSplitThreads / 32);
+                    const uint32_t pj = j < m ? pinfo[j] : 0u;
                     cc[q] = (int)(pj & 0xFFFFu);
-                    dst[q] = pref[j];
-                    eo[q] = cc[q] ? (uint32_t)(tp + j) * (uint32_t)d.tile_post + (pj >> 16) : 0u;     // no piece: entry 0
+                    dst[q] = j < m ? pref[j] : 0;
+                    sp[q] = inter + (size_t)(tp + (j < m ? j : 0)) * d.tile_post + (pj >> 16);
                 }
 #pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    const int last = max(cc[q], 1) - 1;
-                    v[q] = inter[eo[q] + (uint32_t)min(l0, last)];
-                    v2[q] = inter[eo[q] + (uint32_t)min(l0 + 32, last)];
+                for (int q = 0; q < 4; ++q) {      // the first 64 entries of each piece: eight loads in flight
+                    v[q] = l0 < cc[q] ? sp[q][l0] : 0u;
+                    v2[q] = l0 + 32 < cc[q] ? sp[q][l0 + 32] : 0u;
                 }
 #pragma unroll
                 for (int q = 0; q < 4; ++q) {
@@ -296,7 +293,7 @@ __global__ __launch_bounds__(kSplitThreads, kSplitOcc) void idx_bucket_sort_kern
                 }
 #pragma unroll
                 for (int q = 0; q < 4; ++q)
-                    for (int l = l0 + 64; l < cc[q]; l += 32) bufa[dst[q] + l] = inter[eo[q] + (uint32_t)l];
+                    for (int l = l0 + 64; l < cc[q]; l += 32) bufa[dst[q] + l] = sp[q][l];
             }
         }
         for (int i = tid; i < kSplitWaves * nd; i += kSplitThreads) cnt[i] = 0;
@@ -308,21 +305,20 @@ __global__ __launch_bounds__(kSplitThreads, kSplitOcc) void idx_bucket_sort_kern
         unsigned meta[kSplitRounds];       // split_round()
 #pragma unroll
         for (int r = 0; r < kSplitRounds; ++r) {
-            meta[r] = 0u;
-            pos[r] = 0;
-            if (r * 64 < seg) {           // uniform: rounds past the wavefront's share are skipped
-                const int i = wave * seg + r * 64 + lane;       // < kSplitWaves * seg <= kSortCap + 1024: inside the LDS block
-                const uint32_t e = i < n_r ? bufa[i] : 0u;
-                meta[r] = e;
-                pos[r] = d.pos_log[e >> d.S];      // all loads in flight at once; used only after the scan (row 0 if idle)
-            }
+            const int i = wave * seg + r * 64 + lane;
+            const uint32_t e = (r * 64 < seg && i < n_r) ? bufa[i] : 0u;
+            meta[r] = e;
+            pos[r] = d.pos_log[e >> d.S];      // all loads in flight at once; used only after the scan (row 0 if idle)
         }
 #pragma unroll
-        for (int r = 0; r < kSplitRounds; ++r)
-            if (r * 64 < seg) {
-                const bool valid = wave * seg + r * 64 + lane < n_r;
-                meta[r] = split_round<NBITS>(row, meta[r] & mask, valid);
+        for (int r = 0; r < kSplitRounds; ++r) {
+            if (r * 64 >= seg) {          // uniform: this round is past the wavefront's share
+                meta[r] = 0u;
+                continue;
             }
+            const bool valid = wave * seg + r * 64 + lane < n_r;
+            meta[r] = split_round<NBITS>(row, meta[r] & mask, valid);
+        }
         __syncthreads();
         split_scan(cnt, nd, rstart, rcount, wsum);
         if (!multi && tid < nfl) offs[tid] = out_base + rstart[tid];
