@@ -48,6 +48,7 @@ constexpr int kStageB = kFT * RB;
 constexpr int kBiasB = 256;      // the 64 fp32 biases of a pair of stages (one wavefront-wide copy)
 constexpr int kGuard = 4;        // appends possible between two fullness checks
 constexpr float kHintMargin = 0.03f;   // streamed calls start 3 % below the carried bound
+constexpr float kRedoMargin = 0.05f;   // bounds of a head that needed the redo pass are lowered by this much more
 constexpr float kPilotMargin = 0.03f;  // bounds taken from the pilot's single tile are lowered by this much more
 constexpr int kOffBias = kRing * kStageB;
 constexpr int kOffVote = kOffBias + (kRing / 2) * kBiasB;
@@ -122,10 +123,14 @@ __global__ void enc_stream_prep_kernel(int32_t* redo_cnt, unsigned* hint_out, fl
 // `boot`: null for the bounds carried out of the call.  Else (after the pilot launch) the bounds the caller carried
 // in: heads that had one keep it for the main launch, the others start from the pilot's tile, lowered by `extra`
 // because the minimum over one tile of tokens is a weaker bound than the minimum over a whole chunk.
+// `redo_cnt` (bounds carried out of the call only): a head whose carried bound was too high for some token of this
+// call hands on a bound that is lower by kRedoMargin more, so that a drifting stream does not pay a redo pass in
+// every call.
 __global__ void enc_stream_post_kernel(const unsigned* hint_out, const float* hint_sum, float* hint, int n_heads,
-                                       const float* boot, float extra) {
+                                       const float* boot, float extra, const int32_t* redo_cnt) {
     const int h = blockIdx.x * blockDim.x + threadIdx.x;
     if (h >= n_heads) return;
+    if (redo_cnt && redo_cnt[h] > 0) extra += kRedoMargin;
     if (boot && !(boot[2 * h] == -INFINITY && boot[2 * h + 1] == -INFINITY)) {
         hint[2 * h] = boot[2 * h];
         hint[2 * h + 1] = boot[2 * h + 1];
@@ -207,7 +212,7 @@ int s3_encode_fast_stream(EncParams p, float* hint, void* ws, hipStream_t st) {
     int rc = fast_dispatch(p, st);
     if (rc) return rc;
     hipLaunchKernelGGL(enc_stream_post_kernel, dim3(nb), dim3(256), 0, st, p.hint_out, p.hint_sum, hint_mid, p.n_heads,
-                       (const float*)hint, extra);
+                       (const float*)hint, extra, (const int32_t*)nullptr);
     p.hint_in = hint_mid;
     p.mode = 1;
     rc = fast_dispatch(p, st);
@@ -216,7 +221,7 @@ int s3_encode_fast_stream(EncParams p, float* hint, void* ws, hipStream_t st) {
     rc = fast_dispatch(p, st);
     if (rc) return rc;
     hipLaunchKernelGGL(enc_stream_post_kernel, dim3(nb), dim3(256), 0, st, p.hint_out, p.hint_sum, hint, p.n_heads,
-                       (const float*)nullptr, 0.f);
+                       (const float*)nullptr, 0.f, (const int32_t*)p.redo_cnt);
     S3_HIP(hipGetLastError());
     return S3_OK;
 }
