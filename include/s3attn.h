@@ -75,7 +75,8 @@ int s3_sae_encode_topk(const void* x, int dtype, int T, int d_head, const void* 
  *   tau_hint [n_heads][2] fp32, device, read and overwritten: the smallest tau_t / |x_t| and the
  *            smallest tau_t over the tokens of the previous call; only the one that was the tighter
  *            predictor on that call is kept, the other is -INFINITY.  Fill with -INFINITY before
- *            the first chunk of a stream (no bound: same work as s3_sae_encode_topk).
+ *            the first chunk of a stream: a head without a bound has its first 256 tokens (128 for
+ *            k > 32) selected from scratch first, and their thresholds start the rest of the chunk.
  *   ws       s3_sae_encode_topk_stream_workspace(n_heads, T) bytes, 256-byte aligned, device;
  *            scratch, contents meaningless between calls.
  * Shapes the threshold-carrying kernel is not built for (anything but bf16, d_head 128,
