@@ -23,10 +23,18 @@ from paper_2601_17702_amd import synth  # noqa: E402
 
 MFMA_PEAK_TFLOPS = {"bf16": 2500.0, "fp32": 157.3}   # MI355X dense matrix peaks
 HBM_PEAK_GBS = 8000.0
-# HBM bytes per launch of the encoder kernel from the rocprofv3 FETCH_SIZE / WRITE_SIZE runs summarised in
-# profiles/bench_c2_llama8b_hbm_traffic.txt (counter runs cannot be made from inside this script)
-# one chunk call = main pass + redo kernel + the pilot's share (one working pilot launch and 15 empty ones per 16-chunk stream)
-MEASURED_TRAFFIC = {"c2_llama8b": 1374462359 + 592913 + (1131829718 + 15 * 67572) // 16}
+
+
+def measured_traffic(workload: str):
+    """HBM bytes per chunk call of the encoder from the committed counter summary of this workload, if there is one
+    (profiles/encode_<workload>_hbm_traffic.txt, written from two rocprofv3 --pmc runs: counters cannot be read from
+    inside this script).  The file carries a line `traffic_bytes_per_chunk_call = N`; None without the file."""
+    path = os.path.join(ROOT, "profiles", f"encode_{workload}_hbm_traffic.txt")
+    if os.path.exists(path):
+        for line in open(path):
+            if line.lstrip("# ").startswith("traffic_bytes_per_chunk_call"):
+                return int(float(line.split("=")[1].split()[0])), os.path.relpath(path, ROOT)
+    return None, None
 
 
 def gen_inputs(w, torch, threads=16):
@@ -112,45 +120,43 @@ def main():
     ws = torch.empty(index.score_workspace(w.L), dtype=torch.uint8, device="cuda")
     enc_ws = torch.empty(max(s3.sae_encode_topk_stream_workspace(H, w.T), 1), dtype=torch.uint8, device="cuda")
     tau_hint = s3.new_tau_hint(H)
-    ev = lambda: torch.cuda.Event(enable_timing=True)  # noqa: E731
+    # every event of the timed steps exists before the timed region starts; per step: 3 per chunk + 4
+    nev = 3 * w.n_chunks + 4
+    events = [[torch.cuda.Event(enable_timing=True) for _ in range(nev)] for _ in range(args.steps)]
 
-    def step(timers=None):
+    def step(ev=None):
+        """ev: this step's events (chunk c: 3c = before encode, 3c + 1 = after encode, 3c + 2 = after append; then
+        before finalize, after finalize, after query encode, after scoring) or None for an untimed step."""
         index.reset()
         tau_hint.fill_(float("-inf"))            # a new stream: no threshold is carried into its first chunk
-        marks = []
         for c in range(w.n_chunks):
-            if timers is not None:
-                a, b, d = ev(), ev(), ev()
-                a.record()
+            if ev:
+                ev[3 * c].record()
             s3.sae_encode_topk_stream(K[c], W, B, w.k, tau_hint, enc_ws, ids, vals)
-            if timers is not None:
-                b.record()
+            if ev:
+                ev[3 * c + 1].record()
             index.append(ids, base_pos=c * w.T)
-            if timers is not None:
-                d.record()
-                marks.append((a, b, d))
-        f0, f1, f2, f3 = (ev(), ev(), ev(), ev()) if timers is not None else (None,) * 4
-        if timers is not None:
-            f0.record()
+            if ev:
+                ev[3 * c + 2].record()
+        if ev:
+            ev[-4].record()
         index.finalize()
-        if timers is not None:
-            f1.record()
+        if ev:
+            ev[-3].record()
         s3.sae_encode_topk(Q, W, B, w.k, qids, qvals)
-        if timers is not None:
-            f2.record()
+        if ev:
+            ev[-2].record()
         out = index.coactivate_score(qids, qvals, w.L, w.span_len, w.top_b, max_freq=0, nms=True, ws=ws)
-        if timers is not None:
-            f3.record()
-            timers.append((marks, f0, f1, f2, f3))
+        if ev:
+            ev[-1].record()
         return out
 
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
-    timers = []
     t0 = time.perf_counter()
-    for _ in range(args.steps):
-        out = step(timers)
+    for i in range(args.steps):
+        out = step(events[i])
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
 
@@ -160,11 +166,13 @@ def main():
         dst.copy_(src)
         torch.cuda.synchronize()
 
-    enc_ms = [a.elapsed_time(b) for marks, *_ in timers for a, b, _ in marks]
-    app_ms = [b.elapsed_time(d) for marks, *_ in timers for _, b, d in marks]
-    fin_ms = [f0.elapsed_time(f1) for _, f0, f1, _, _ in timers]
-    qenc_ms = [f1.elapsed_time(f2) for _, _, f1, f2, _ in timers]
-    score_ms = [f2.elapsed_time(f3) for _, _, _, f2, f3 in timers]
+    nc = w.n_chunks
+    enc_ms = [e[3 * c].elapsed_time(e[3 * c + 1]) for e in events for c in range(nc)]
+    app_ms = [e[3 * c + 1].elapsed_time(e[3 * c + 2]) for e in events for c in range(nc)]
+    fin_ms = [e[-4].elapsed_time(e[-3]) for e in events]
+    qenc_ms = [e[-3].elapsed_time(e[-2]) for e in events]
+    score_ms = [e[-2].elapsed_time(e[-1]) for e in events]
+    scan_ms = float(np.mean([e[0].elapsed_time(e[-3]) for e in events]))    # encode + Top-k + index of one context
     enc_avg = float(np.mean(enc_ms))
     flop_per_launch = 2.0 * w.d_head * w.n_feat * w.T * H       # encoder GEMM of one chunk, all heads
     achieved = flop_per_launch / (enc_avg * 1e-3) / 1e12
@@ -172,7 +180,7 @@ def main():
     ms_per_step = dt / args.steps * 1e3
 
     # algorithmic HBM bytes of the index build and of scoring (every byte that has to move once)
-    idx_bytes = 2.0 * H * w.L * w.k * 4                          # ids in, postings out
+    idx_bytes = 2.0 * H * w.L * w.k * 4 + 4.0 * H * (w.n_feat + 1)   # ids in, postings and offsets out
     post_bytes = 0.0
     qh = qids.cpu().numpy()
     for h in range(H):
@@ -181,9 +189,17 @@ def main():
         post_bytes += 4.0 * float((off[f + 1] - off[f]).sum())   # posting lists named by this head's queries
     score_bytes = post_bytes + 2.0 * H * w.nq * w.k * 4 + 4.0 * w.L
     idx_ms = float(np.sum(app_ms)) / args.steps + float(np.mean(fin_ms))
+    traffic, traffic_src = measured_traffic(w.name)
+
+    def hbm(nbytes, ms):
+        return {"bound": "hbm", "bytes": nbytes, "ms": ms, "achieved": nbytes / ms / 1e6, "peak": HBM_PEAK_GBS,
+                "unit": "GB/s", "frac": nbytes / ms / 1e6 / HBM_PEAK_GBS}
+
     res = {
         "metric": "scanned tokens\u00b7heads/sec (encode+TopK+index) at Llama-8B shape; % MFMA/HBM peak",
-        "value": w.token_heads / (ms_per_step * 1e-3),
+        # the metric's own stages: every chunk's encode + Top-k + append, then finalize (events inside the timed steps);
+        # the query encode and the scoring that complete a step are timed and reported separately below
+        "value": w.token_heads / (scan_ms * 1e-3),
         "unit": "tokens\u00b7heads/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
@@ -191,18 +207,19 @@ def main():
         "config": {"workload": w.name, "layers": w.layers, "kv_heads": w.kv_heads, "tokens": w.L, "chunk": w.T,
                    "d_head": w.d_head, "n_feat": w.n_feat, "k": w.k, "queries_per_kv_head": w.nq,
                    "span_len": w.span_len, "top_b": w.top_b},
+        "scan_ms_per_step": scan_ms,
+        "whole_path_tokens_heads_per_s": w.token_heads / (ms_per_step * 1e-3),
         "stages_ms": {"encode_topk": float(np.sum(enc_ms)) / args.steps, "index_append": float(np.sum(app_ms)) / args.steps,
                       "index_finalize": float(np.mean(fin_ms)), "query_encode": float(np.mean(qenc_ms)),
                       "coactivate_score": float(np.mean(score_ms))},
         "roofline": {"kernel": ("k32" if w.k <= 32 else "k64") + "::sae_encode_topk_fast_kernel<0>", "bound": "mfma", "achieved": achieved, "peak": peak,
-                     "unit": "TFLOP/s", "frac": achieved / peak, "traffic": MEASURED_TRAFFIC.get(w.name),
+                     "unit": "TFLOP/s", "frac": achieved / peak, "traffic": traffic, "traffic_source": traffic_src,
                      "launch_ms": enc_avg, "flop_per_launch": flop_per_launch},
         "stage_rooflines": {
-            "index_build": {"bound": "hbm", "bytes": idx_bytes, "ms": idx_ms, "achieved": idx_bytes / idx_ms / 1e6,
-                            "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": idx_bytes / idx_ms / 1e6 / HBM_PEAK_GBS},
-            "coactivate_score": {"bound": "hbm", "bytes": score_bytes, "ms": float(np.mean(score_ms)),
-                                 "achieved": score_bytes / float(np.mean(score_ms)) / 1e6, "peak": HBM_PEAK_GBS,
-                                 "unit": "GB/s", "frac": score_bytes / float(np.mean(score_ms)) / 1e6 / HBM_PEAK_GBS}},
+            "encode_topk": {"bound": "mfma", "flop": flop_per_launch * nc, "ms": float(np.sum(enc_ms)) / args.steps,
+                            "achieved": achieved, "peak": peak, "unit": "TFLOP/s", "frac": achieved / peak},
+            "index_build": hbm(idx_bytes, idx_ms),
+            "coactivate_score": hbm(score_bytes, float(np.mean(score_ms)))},
         "spans_found": int(out[2].item()),
     }
     if not args.no_cpu_baseline:

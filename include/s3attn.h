@@ -57,8 +57,10 @@ const char* s3_last_error(void);
  * row always has exactly k distinct ids; vals = max(z, 0).  Within a row the order is
  * (z descending, id ascending).  z is accumulated in fp32 and never written to memory.
  * Inputs are assumed finite.
- * Limits: d_head in {64, 128, 256}; 1 <= k <= min(n_feat, S3_MAX_K); n_feat <= S3_MAX_FEAT;
- * T >= 0 (T == 0 is a no-op); n_heads >= 1.  Otherwise S3_EINVAL.  No workspace is needed.
+ * Limits: d_head in {64, 128, 256}; 1 <= k <= min(n_feat, S3_MAX_K), and k <= 62 for fp32 with
+ * d_head 256 (the candidate lists of that kernel would not fit the 160 KB of LDS);
+ * n_feat <= S3_MAX_FEAT; T >= 0 (T == 0 is a no-op); n_heads >= 1.  Otherwise S3_EINVAL.
+ * No workspace is needed (so there is no workspace query for this call).
  */
 int s3_sae_encode_topk(const void* x, int dtype, int T, int d_head, const void* w_enc,
                        const float* b_enc, int n_feat, int k, int n_heads, int32_t* ids,
@@ -159,7 +161,10 @@ int s3_index_build(const int32_t* ids, const int32_t* positions, int T, int k, i
  * Sums are accumulated in 64-bit fixed point, so the result is independent of execution order
  * (bit-identical from run to run) and W[s] is exactly the sum of its members before the final
  * rounding to fp32.
- * Limits: 1 <= span_len; 1 <= top_b <= 1024; nq >= 0; qvals finite and >= 0.
+ * Limits: 1 <= span_len; 1 <= top_b <= 1024; nq >= 0; nq * k <= 2^20; qvals finite and >= 0;
+ * ceil(log2(n_heads * k)) + ceil(log2(min(span_len, n_positions))) <= 36, so that a window's
+ * fixed-point sum cannot overflow 64 bits while weights keep at least 22 significant bits
+ * (S3_EINVAL otherwise).
  */
 size_t s3_coactivate_score_workspace(const s3_index* idx, int64_t n_positions);
 int s3_coactivate_score(const s3_index* idx, const int32_t* qids, const float* qvals, int nq,

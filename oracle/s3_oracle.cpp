@@ -88,6 +88,25 @@ int orc_encode_topk(const void* x, int dtype, int T, int d, const void* w, const
     return 0;
 }
 
+// Sec. 3.3, encoder equation at chosen entries only: z[t, j] = W_enc[ids[t, j]] . x[t] + b[ids[t, j]] (b_dec folded
+// as above), fp64, channels ascending.  Lets a test look up the pre-activation of any feature of any row without
+// the dense [T, n_feat] array.  ids [T, m] in [0, n_feat), z [T, m].
+int orc_preact_at(const void* x, int dtype, int T, int d, const void* w, const float* b, int n_feat,
+                  const int32_t* ids, int m, double* z) {
+    if (T < 0 || d <= 0 || n_feat <= 0 || m < 0) return -1;
+    for (size_t i = 0; i < (size_t)T * m; ++i)
+        if (ids[i] < 0 || ids[i] >= n_feat) return -1;
+#pragma omp parallel for schedule(static)
+    for (int t = 0; t < T; ++t)
+        for (int j = 0; j < m; ++j) {
+            const size_t f = (size_t)ids[(size_t)t * m + j];
+            double acc = 0.0;
+            for (int c = 0; c < d; ++c) acc += widen(x, dtype, (size_t)t * d + c) * widen(w, dtype, f * d + c);
+            z[(size_t)t * m + j] = acc + (double)b[f];
+        }
+    return 0;
+}
+
 // Sec. 3.4, index update equation: for every feature f in F_t, I[f] <- I[f] U {t}, tokens taken
 // in the order given; positions are absolute.
 void* orc_index_new(void) { return new Index(); }

@@ -1,7 +1,11 @@
 """ctypes loader for the CPU oracle (oracle/s3_oracle.cpp).  TEST INFRASTRUCTURE ONLY.
 
 Imported by tests/, by the smoke check and by the benchmark's cpu_baseline leg; never by the
-product package.  Argument marshalling only: all arithmetic is in the C++ file.
+product package.  Argument marshalling for the C++ file, which holds the arithmetic -- with one exception,
+score_dense at the end: the scoring equation of Sec. 3.5 evaluated token by token in numpy, for contexts
+where building every head's std::map postings on the host would take too long.  It is pinned by the
+hand-computed case, by App. D.2's set-intersection sum written out with Python sets, and against the
+postings form (tests/test_oracle_pins.py).
 """
 from __future__ import annotations
 
@@ -31,6 +35,8 @@ def lib():
         vp, i32, i64 = C.c_void_p, C.c_int32, C.c_int64
         L.orc_encode_topk.argtypes = [vp, C.c_int, C.c_int, C.c_int, vp, vp, C.c_int, C.c_int, vp, vp, vp, vp, vp]
         L.orc_encode_topk.restype = C.c_int
+        L.orc_preact_at.argtypes = [vp, C.c_int, C.c_int, C.c_int, vp, vp, C.c_int, vp, C.c_int, vp]
+        L.orc_preact_at.restype = C.c_int
         L.orc_index_new.restype = vp
         L.orc_index_free.argtypes = [vp]
         L.orc_index_append.argtypes = [vp, vp, vp, C.c_int, C.c_int]
@@ -76,6 +82,23 @@ def encode_topk(x, w, b, k, dtype, want_dense=False):
     if rc != 0:
         raise ValueError("orc_encode_topk: invalid arguments")
     return {"ids": ids, "vals": vals, "zsel": zsel, "gap": gap, "z": z}
+
+
+def preact_at(x, w, b, ids, dtype):
+    """Pre-activations z[t, j] of the features ids[t, j] (int32 [T, m]) for the stored x [T, d], w [n_feat, d],
+    b [n_feat] float32: float64 [T, m]."""
+    x = np.ascontiguousarray(x)
+    w = np.ascontiguousarray(w)
+    b = np.ascontiguousarray(b, dtype=np.float32)
+    ids = np.ascontiguousarray(ids, dtype=np.int32)
+    want = np.float32 if dtype == "fp32" else np.uint16
+    assert x.dtype == want and w.dtype == want and ids.ndim == 2 and ids.shape[0] == x.shape[0]
+    z = np.empty(ids.shape, np.float64)
+    rc = lib().orc_preact_at(_p(x), _dt(dtype), x.shape[0], x.shape[1], _p(w), _p(b), w.shape[0], _p(ids),
+                             ids.shape[1], _p(z))
+    if rc != 0:
+        raise ValueError("orc_preact_at: invalid arguments or feature id outside [0, n_feat)")
+    return z
 
 
 class Index:
@@ -159,10 +182,9 @@ def score_dense(ids, qids, qvals, n_feat, max_freq=0):
         freq = np.bincount(ids[h].reshape(-1), minlength=n_feat)
         act = np.zeros(n_feat, np.float64)
         np.add.at(act, np.asarray(qids[h]).reshape(-1), np.asarray(qvals[h], np.float64).reshape(-1))
-        w = np.zeros(n_feat, np.float64)
-        for fr in np.unique(freq[act != 0]):
-            if fr > 0 and not (max_freq > 0 and fr > max_freq):
-                sel = (freq == fr) & (act != 0)
-                w[sel] = act[sel] * idf(int(fr))
+        # one IDF value per distinct list length (the C++ orc_idf), 0 for lists the rule skips and for empty ones
+        lengths, which = np.unique(freq, return_inverse=True)
+        table = np.array([idf(int(fr)) if fr > 0 and not (max_freq > 0 and fr > max_freq) else 0.0 for fr in lengths])
+        w = act * table[which.reshape(-1)]
         S += w[ids[h]].sum(axis=1)
     return S

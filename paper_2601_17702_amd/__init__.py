@@ -180,6 +180,13 @@ class Index:
         _check(lib().s3_index_export(self._h, head, _ptr(o), _ptr(p) if n.value else None, _stream()))
         return o, p
 
+    def csr_offsets(self, head: int):
+        """Copy of one head's offsets [n_feat + 1] only."""
+        import torch
+        o = torch.empty(self.n_feat + 1, dtype=torch.int32, device="cuda")
+        _check(lib().s3_index_export(self._h, head, _ptr(o), None, _stream()))
+        return o
+
     def score_workspace(self, n_positions: int) -> int:
         return int(lib().s3_coactivate_score_workspace(self._h, n_positions))
 

@@ -8,18 +8,21 @@ import subprocess
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libs3attn.so")
-FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
+FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fvisibility=hidden",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wno-unused-result"]
 
 
-def build(verbose: bool = False) -> str:
+def build(verbose: bool = False, tuning_lib: str | None = None) -> str:
+    """Compile every csrc/*.hip and link libs3attn.so.  tuning_lib: path of a second library to build instead, with
+    -DS3_TUNING (environment knobs, kernels with parts compiled out, cycle counters: measurement tooling only)."""
     srcs = sorted(glob.glob(os.path.join(CSRC, "*.hip")))
     objs = []
     procs = []
+    extra = ["-DS3_TUNING"] if tuning_lib else []
     for s in srcs:
-        o = s[:-4] + ".o"
+        o = s[:-4] + (".tuning.o" if tuning_lib else ".o")
         objs.append(o)
-        procs.append((s, subprocess.Popen(["hipcc", *FLAGS, "-c", s, "-o", o], stderr=subprocess.PIPE, text=True)))
+        procs.append((s, subprocess.Popen(["hipcc", *FLAGS, *extra, "-c", s, "-o", o], stderr=subprocess.PIPE, text=True)))
     for s, p in procs:
         _, err = p.communicate()
         err = "\n".join(l for l in err.splitlines() if "packed-fp32-ops" not in l)
@@ -27,8 +30,9 @@ def build(verbose: bool = False) -> str:
             raise RuntimeError(f"hipcc failed on {s}:\n{err}")
         if verbose and err.strip():
             print(err)
-    subprocess.check_call(["hipcc", "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs])
-    return LIB
+    out = tuning_lib or LIB
+    subprocess.check_call(["hipcc", "--offload-arch=gfx950", "-shared", "-fPIC", "-o", out, *objs])
+    return out
 
 
 if __name__ == "__main__":

@@ -334,11 +334,8 @@ int launch(const EncParams& p, int n_heads, hipStream_t st) {
     constexpr int ROWB = DH * F::ES + 16;
     size_t lds = 2 * kFT * ROWB + 2 * kFT * sizeof(float) + (size_t)kWaves * p.capt * 32 * (sizeof(float) + sizeof(uint16_t));
     auto kern = sae_encode_topk_kernel<DT, DH>;
-    static bool attr_set = false;      // once per instantiation: allow the full 160 KB of LDS
-    if (!attr_set) {
-        S3_HIP(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024));
-        attr_set = true;
-    }
+    static S3LdsOnce once;             // per instantiation: allow the full 160 KB of LDS
+    if (int rc = s3_allow_lds(once, (const void*)kern, 160 * 1024)) return rc;
     if (lds > 160 * 1024) return s3_fail(S3_EINVAL, "s3_sae_encode_topk: candidate lists need %zu bytes of LDS", lds);
     dim3 grid((unsigned)(n_heads * p.tiles_per_head));
     hipLaunchKernelGGL(kern, grid, dim3(kThreads), lds, st, p);
@@ -348,10 +345,12 @@ int launch(const EncParams& p, int n_heads, hipStream_t st) {
 
 }  // namespace
 
+#ifdef S3_TUNING
 int env_int(const char* name, int dflt) {
     const char* s = getenv(name);
     return s && *s ? atoi(s) : dflt;
 }
+#endif
 
 static int encode_impl(const char* who, const void* x, int dtype, int T, int d_head, const void* w_enc, const float* b_enc,
                        int n_feat, int k, int n_heads, int32_t* ids, float* vals, float* tau_hint, void* ws,
@@ -376,15 +375,22 @@ static int encode_impl(const char* who, const void* x, int dtype, int T, int d_h
     EncParams p;
     p.x = (const char*)x; p.w = (const char*)w_enc; p.b = b_enc; p.ids = ids; p.vals = vals;
     p.T = T; p.n_feat = n_feat; p.k = k; p.n_heads = n_heads;
+    p.ablate = 0;
+    bool fast = s3_encode_fast_ok(dtype, d_head, n_feat, k);
+#ifdef S3_TUNING
     p.ablate = env_int("S3_ENC_ABLATE", 0);
+    if (env_int("S3_ENC_GENERIC", 0)) fast = false;
+#endif
     hipStream_t st = (hipStream_t)stream;
-    if (s3_encode_fast_ok(dtype, d_head, n_feat, k) && env_int("S3_ENC_GENERIC", 0) == 0)
+    if (fast)
         return tau_hint ? s3_encode_fast_stream(p, tau_hint, ws, st) : s3_encode_fast_launch(p, st);
     p.tiles_per_head = (T + kTokWG - 1) / kTokWG;
     // list capacity per token: k survivors + headroom for one tile + room for new candidates between refreshes
     int capt = k + kHeadroom + (k <= 32 ? 16 : 32);
+#ifdef S3_TUNING
     capt = env_int("S3_ENC_CAPT", capt);
     if (capt < k + kHeadroom + 4 || capt > 512) return s3_fail(S3_EINVAL, "%s: bad S3_ENC_CAPT %d", who, capt);
+#endif
     p.capt = capt;
 #define S3_CASE(DT, DH) if (dtype == DT && d_head == DH) return launch<DT, DH>(p, n_heads, st);
     S3_CASE(S3_BF16, 64) S3_CASE(S3_BF16, 128) S3_CASE(S3_BF16, 256)

@@ -59,11 +59,14 @@ typedef __attribute__((address_space(3))) void lds_void;
 typedef __attribute__((address_space(3))) char lds_char;
 typedef __attribute__((address_space(1))) const void glb_cvoid;
 
-// compile-time ablation masks of the tuning builds (0 in the product kernel)
+// compile-time ablation masks: the product library instantiates the kernels with 0 only; builds with -DS3_TUNING
+// (measurement tooling, never shipped) also instantiate kernels without appends and with per-phase cycle counters
 constexpr int kNoHits = 1, kProfile = 16;
 
+#ifdef S3_TUNING
 // kProfile build: cycles per phase, summed over the steps of wavefronts 0 and 4 of workgroup 0
 __device__ unsigned long long s3_prof[32];
+#endif
 
 __device__ __forceinline__ void lds_store_u32(unsigned addr, unsigned v) {
     asm volatile("ds_write_b32 %0, %1" ::"v"(addr), "v"(v) : "memory");
@@ -204,8 +207,12 @@ int s3_encode_fast_stream(EncParams p, float* hint, void* ws, hipStream_t st) {
     p.redo_list = (int32_t*)take((size_t)p.n_heads * p.T * 4);
     const int nb = (3 * p.n_heads + 255) / 256;
     hipLaunchKernelGGL(enc_stream_prep_kernel, dim3(nb), dim3(256), 0, st, p.redo_cnt, p.hint_out, p.hint_sum, p.n_heads);
-    p.margin = (float)env_int("S3_ENC_MARGIN", (int)(kHintMargin * 1000.f + 0.5f)) * 1e-3f;   // per mille, tuning
-    const float extra = (float)env_int("S3_ENC_PILOT_MARGIN", (int)(kPilotMargin * 1000.f + 0.5f)) * 1e-3f;
+    p.margin = kHintMargin;
+    float extra = kPilotMargin;
+#ifdef S3_TUNING
+    p.margin = (float)env_int("S3_ENC_MARGIN", (int)(kHintMargin * 1000.f + 0.5f)) * 1e-3f;   // per mille
+    extra = (float)env_int("S3_ENC_PILOT_MARGIN", (int)(kPilotMargin * 1000.f + 0.5f)) * 1e-3f;
+#endif
     p.boot_in = hint;
     p.hint_in = nullptr;
     p.mode = 3;
@@ -228,28 +235,35 @@ int s3_encode_fast_stream(EncParams p, float* hint, void* ws, hipStream_t st) {
 
 static int fast_dispatch(EncParams p, hipStream_t st) {
     const bool small_k = p.k <= k32::kMaxK;
+    p.soft = small_k ? k32::kSoftDefault : k64::kSoftDefault;      // list length that asks for a voted refresh
+#ifdef S3_TUNING
     const int capl = small_k ? k32::CAPL : k64::CAPL;
-    p.soft = env_int("S3_ENC_SOFT", small_k ? k32::kSoftDefault : k64::kSoftDefault);   // voted refresh threshold (0 = off)
+    p.soft = env_int("S3_ENC_SOFT", p.soft);                       // 0 = no voted refreshes
     if (p.soft < 0 || p.soft > capl - kGuard) return s3_fail(S3_EINVAL, "s3_sae_encode_topk: bad S3_ENC_SOFT");
     if (small_k) {
-        switch (p.ablate) {       // tuning builds: parts of the kernel compiled out (results are then meaningless)
-            case 0: return k32::launch_fast<0>(p, st);
+        switch (p.ablate) {       // parts of the kernel compiled out (results are then meaningless)
+            case 0: break;
             case 1: return k32::launch_fast<kNoHits>(p, st);
             case 16: return k32::launch_fast<kProfile>(p, st);
             case 17: return k32::launch_fast<kProfile | kNoHits>(p, st);
+            default: return s3_fail(S3_EINVAL, "s3_sae_encode_topk: S3_ENC_ABLATE %d is not built", p.ablate);
         }
     } else {
         switch (p.ablate) {
-            case 0: return k64::launch_fast<0>(p, st);
+            case 0: break;
             case 1: return k64::launch_fast<kNoHits>(p, st);
+            default: return s3_fail(S3_EINVAL, "s3_sae_encode_topk: S3_ENC_ABLATE %d is not built", p.ablate);
         }
     }
-    return s3_fail(S3_EINVAL, "s3_sae_encode_topk: S3_ENC_ABLATE %d is not built", p.ablate);
+#endif
+    return small_k ? k32::launch_fast<0>(p, st) : k64::launch_fast<0>(p, st);
 }
 
-// Tuning aid (not part of the public interface): phase cycle sums of the last S3_ENC_ABLATE=16/17 launch.
+#ifdef S3_TUNING
+// Measurement aid of the tuning build: phase cycle sums of the last S3_ENC_ABLATE=16/17 launch.
 extern "C" int s3_debug_profile(unsigned long long* out32) {
     S3_HIP(hipDeviceSynchronize());
     S3_HIP(hipMemcpyFromSymbol(out32, HIP_SYMBOL(s3_prof), sizeof(unsigned long long) * 32));
     return S3_OK;
 }
+#endif

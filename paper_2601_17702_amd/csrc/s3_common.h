@@ -4,7 +4,12 @@
 #include <stddef.h>
 #include <stdint.h>
 
+#include <mutex>
+
+// The library is built with -fvisibility=hidden: only what the public header declares is exported.
+#pragma GCC visibility push(default)
 #include "../../include/s3attn.h"
+#pragma GCC visibility pop
 
 int s3_fail(int code, const char* fmt, ...);   // records the thread-local message, returns code
 
@@ -14,6 +19,14 @@ int s3_fail(int code, const char* fmt, ...);   // records the thread-local messa
         if (e_ != hipSuccess)                                                            \
             return s3_fail(S3_EHIP, "%s failed: %s", #call, hipGetErrorString(e_));      \
     } while (0)
+
+// Raises a kernel's dynamic-LDS limit once per device (thread-safe).  One S3LdsOnce object per kernel.
+constexpr int kS3MaxDevices = 64;
+struct S3LdsOnce {
+    std::once_flag flag[kS3MaxDevices];
+    hipError_t err[kS3MaxDevices];
+};
+int s3_allow_lds(S3LdsOnce& once, const void* kernel, int bytes);
 
 static inline size_t s3_align(size_t n, size_t a = 256) { return (n + a - 1) / a * a; }
 static inline int s3_ceil_log2(unsigned v) {
@@ -68,7 +81,8 @@ struct EncParams {
     const float* b;
     int32_t* ids;
     float* vals;
-    int T, n_feat, k, n_heads, capt, tiles_per_head, ablate;
+    int T, n_feat, k, n_heads, capt, tiles_per_head;
+    int ablate;    // tuning builds (-DS3_TUNING) only: parts of the kernel compiled out; always 0 in the product
     int soft;      // fast path: list length per lane that asks for a workgroup-wide refresh (0: off)
     // streamed calls (threshold carried from the previous chunk), fast path only
     float margin;              // relative margin below the carried bound
@@ -82,7 +96,9 @@ struct EncParams {
     int32_t* redo_cnt;         // [n_heads]
 };
 
-int env_int(const char* name, int dflt);
+#ifdef S3_TUNING
+int env_int(const char* name, int dflt);      // tuning knobs are read from the environment in tuning builds only
+#endif
 bool s3_encode_fast_ok(int dtype, int d_head, int n_feat, int k);   // shapes the fast kernel is built for
 int s3_encode_fast_launch(EncParams p, hipStream_t st);
 size_t s3_encode_fast_stream_workspace(int n_heads, int T);

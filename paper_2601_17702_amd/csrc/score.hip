@@ -503,8 +503,12 @@ extern "C" int s3_coactivate_score(const s3_index* idx, const int32_t* qids, con
     a.len = (int)(span_len < n_positions ? span_len : n_positions);
     a.nW = n_positions - a.len + 1;
     a.top_b = top_b; a.nms = nms ? 1 : 0; a.max_freq = max_freq;
-    a.hb = s3_ceil_log2((unsigned)(a.n_heads * a.k)) + 4;   // up to 16 x n_heads x k contributions per position
-    if (a.hb > 40) return s3_fail(S3_EINVAL, "s3_coactivate_score: n_heads * k too large");
+    // Headroom of the 64-bit fixed point: a position sums at most n_heads * k weights, a window at most span_len
+    // positions; four more bits are spare.  Weights keep 62 - hb significant bits below the largest one.
+    a.hb = s3_ceil_log2((unsigned)(a.n_heads * a.k)) + s3_ceil_log2((unsigned)a.len) + 4;
+    if (a.hb > 40)
+        return s3_fail(S3_EINVAL, "s3_coactivate_score: n_heads * k * span_len too large for the 64-bit fixed-point sums "
+                                  "(log2 of it, rounded up per factor, must be <= 36)");
     a.sc = (Scal*)(base + l.sc);
     a.sfix = (unsigned long long*)(base + l.sfix);
     a.qacc = (unsigned long long*)(base + l.qacc);
@@ -530,12 +534,8 @@ extern "C" int s3_coactivate_score(const s3_index* idx, const int32_t* qids, con
         const size_t nhf = (size_t)a.n_heads * a.n_feat;
         hipLaunchKernelGGL(sc_qw_kernel, dim3((unsigned)((nhf + 256 * kQwPer - 1) / (256 * kQwPer))), dim3(256), 0, st, a);
         if (a.npb) {
-            static bool attr_set = false;
-            if (!attr_set) {
-                S3_HIP(hipFuncSetAttribute((const void*)sc_scatter_lds_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                           kMaxPB * 8));
-                attr_set = true;
-            }
+            static S3LdsOnce once;
+            if (int rc = s3_allow_lds(once, (const void*)sc_scatter_lds_kernel, kMaxPB * 8)) return rc;
             hipLaunchKernelGGL(sc_scatter_lds_kernel, dim3((unsigned)a.npb, (unsigned)a.ngroup), dim3(kScatterThreads),
                                (size_t)a.pb * 8, st, a);
             if (a.ngroup > 1) hipLaunchKernelGGL(sc_reduce_kernel, dim3(blocks((size_t)a.L, 256)), dim3(256), 0, st, a);

@@ -6,6 +6,10 @@ from paper_2601_17702_amd import synth
 
 REL_TOL = 2e-3        # activations and scores: bf16 inputs, fp32 accumulation
 TIE_GAP = 1e-3        # a row may differ from the oracle only if its k-th/(k+1)-th relative gap is below this
+# The kernel accumulates d_head <= 256 products in fp32: |dz| <= d_head * 2^-24 * sum|x_c w_c|, a few 1e-5 of |z| at
+# the k-th value of these workloads.  Rows whose id set really differs must therefore come from the rows whose
+# oracle gap is below FLIP_GAP; their number is the budget for differing rows.
+FLIP_GAP = 1e-4
 
 
 def to_gpu(a: np.ndarray, dtype: str):
@@ -22,34 +26,46 @@ def head_inputs(w: synth.Workload, heads, chunk=0):
     return x, W, b
 
 
-def check_encode(ids_g, vals_g, x, W, b, k, dtype, want_dense=False):
-    """ids_g/vals_g [H, T, k] numpy from the GPU; x/W/b stored host arrays.  Returns (tie_rows, rows)."""
-    H, T = ids_g.shape[:2]
+def check_encode_rows(gi, gv, x, W, b, k, dtype, tag=""):
+    """One head: gi/gv [T, k] from the GPU, x [T, d] / W [n_feat, d] / b [n_feat] as stored.  Every row is checked:
+    k distinct ids; the order (z descending, id ascending) and every value against the oracle's pre-activation of
+    that very feature; the id set equal to the oracle's, or -- only where the oracle's k-th/(k+1)-th gap is below
+    TIE_GAP -- made of features whose pre-activation is within that gap of the k-th largest.
+    Returns (rows whose id set differs, rows with gap < FLIP_GAP)."""
+    o = orc.encode_topk(x, W, b, k, dtype)
+    zg = orc.preact_at(x, W, b, gi, dtype)                      # oracle pre-activation of every id the GPU returned
+    T = gi.shape[0]
     ties = 0
+    srt = np.sort(gi, axis=1)
+    assert srt.min() >= 0 and srt.max() < W.shape[0] and np.all(np.diff(srt, axis=1) > 0), f"{tag}: ids not distinct / in range"
+    want_v = np.maximum(zg, 0.0)
+    bad = np.abs(gv - want_v) > REL_TOL * np.abs(want_v) + 1e-6
+    assert not bad.any(), f"{tag}: value mismatch at (row, slot) {np.argwhere(bad)[:4].tolist()}"
+    # order: z non-increasing up to rounding; equal oracle values in ascending id
+    dz = np.diff(zg, axis=1)
+    assert np.all(dz <= REL_TOL * np.abs(zg[:, :-1]) + 1e-6), f"{tag}: rows not in descending order"
+    assert np.all((dz != 0) | (np.diff(gi, axis=1) > 0)), f"{tag}: equal pre-activations not in ascending id order"
+    for t in np.flatnonzero((gi != o["ids"]).any(axis=1)):
+        g_row, o_row = gi[t], o["ids"][t]
+        if set(g_row.tolist()) == set(o_row.tolist()):
+            continue                                           # same set: the order was checked above
+        zk = o["zsel"][t, -1]
+        assert o["gap"][t] < TIE_GAP, (f"{tag} row {t}: id set differs, gap {o['gap'][t]:.3e}: gpu {sorted(g_row.tolist())} "
+                                       f"oracle {sorted(o_row.tolist())}")
+        # whatever was picked instead is as good as the k-th value, within the gap
+        assert zg[t].min() >= zk - TIE_GAP * abs(zk), f"{tag} row {t}: substituted feature is below the k-th value"
+        ties += 1
+    return ties, int((o["gap"] < FLIP_GAP).sum())
+
+
+def check_encode(ids_g, vals_g, x, W, b, k, dtype):
+    """ids_g/vals_g [H, T, k] numpy from the GPU; x/W/b stored host arrays.  Returns (rows whose id set differs from
+    the oracle's, rows); asserts that no more rows differ than the oracle has rows with a gap below FLIP_GAP."""
+    H, T = ids_g.shape[:2]
+    ties = near = 0
     for h in range(H):
-        o = orc.encode_topk(x[h], W[h], b[h], k, dtype, want_dense=want_dense)
-        for t in range(T):
-            gi, oi = ids_g[h, t], o["ids"][t]
-            assert len(set(gi.tolist())) == k, f"head {h} row {t}: ids not distinct"
-            assert np.all(np.diff(vals_g[h, t]) <= 0), f"head {h} row {t}: values not in descending order"
-            if not np.array_equal(gi, oi):
-                if set(gi.tolist()) == set(oi.tolist()):
-                    # same set, different order: only allowed among (near-)equal values
-                    zo = dict(zip(oi.tolist(), o["zsel"][t].tolist()))
-                    zg = np.array([zo[f] for f in gi.tolist()])
-                    assert np.all(np.diff(zg) <= REL_TOL * np.abs(zg[:-1]) + 1e-6), f"head {h} row {t}: wrong order"
-                else:
-                    assert o["gap"][t] < TIE_GAP, (
-                        f"head {h} row {t}: id set differs, gap {o['gap'][t]:.3e}: gpu {sorted(gi.tolist())} "
-                        f"oracle {sorted(oi.tolist())}")
-                    ties += 1
-                    if want_dense:   # whatever was picked instead must be as good as the k-th value within the gap
-                        zk = o["zsel"][t, -1]
-                        assert o["z"][t, gi].min() >= zk - TIE_GAP * abs(zk)
-            common = {f: j for j, f in enumerate(oi.tolist())}
-            for j, f in enumerate(gi.tolist()):
-                if f in common:
-                    ov = o["vals"][t, common[f]]
-                    assert abs(vals_g[h, t, j] - ov) <= REL_TOL * abs(ov) + 1e-6, (
-                        f"head {h} row {t} feature {f}: {vals_g[h, t, j]} vs {ov}")
+        t_, n_ = check_encode_rows(ids_g[h], vals_g[h], x[h], W[h], b[h], k, dtype, tag=f"head {h}")
+        ties += t_
+        near += n_
+    assert ties <= near, f"{ties} rows differ from the oracle but only {near} rows have a gap below {FLIP_GAP}"
     return ties, H * T

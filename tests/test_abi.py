@@ -23,6 +23,33 @@ def test_library_exports_every_declared_symbol():
         assert hasattr(lib, n), f"{n} declared in include/s3attn.h but not exported"
 
 
+def test_library_exports_nothing_but_the_declared_symbols():
+    """Every dynamic symbol the library defines with the s3 prefix (in any case, mangled or not) is declared in the
+    header: no tuning hook, no internal helper leaks out."""
+    import subprocess
+    out = subprocess.check_output(["nm", "-D", "--defined-only", s3.LIB_PATH], text=True)
+    exported = sorted(line.split()[-1] for line in out.splitlines() if "s3_" in line.lower())
+    assert exported == declared_symbols()
+
+
+def test_no_environment_reads_in_the_product_sources():
+    """Tuning knobs exist only under -DS3_TUNING: outside such blocks no source reads the environment."""
+    import glob
+    for path in glob.glob(os.path.join(ROOT, "paper_2601_17702_amd", "csrc", "*")):
+        if not path.endswith((".hip", ".h", ".inc")):
+            continue
+        depth, tuning = [], 0
+        for line in open(path):
+            t = line.strip()
+            if t.startswith("#if"):
+                depth.append("S3_TUNING" in t)
+                tuning += depth[-1]
+            elif t.startswith("#endif") and depth:
+                tuning -= depth.pop()
+            elif not tuning:
+                assert "getenv" not in t and "env_int" not in t, f"{path}: {t}"
+
+
 def test_host_side_argument_validation():
     L = s3.lib()
     one = C.c_void_p(256)           # non-null, never dereferenced: validation fails first

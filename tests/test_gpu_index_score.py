@@ -188,6 +188,8 @@ def test_tiny_case_by_hand():
     (1, 300, 8, 64, 5, 1, 40, 0, True),              # span of one token
     (1, 90, 8, 64, 5, 500, 4, 0, True),              # span longer than the context: a single window
     (2, 1000, 4, 50, 6, 128, 64, 0, True),           # more spans asked for than disjoint windows exist
+    (2, 1000, 4, 50, 6, 512, 4, 0, True),            # long windows over few heads: the windows' fixed-point sums need
+    (1, 3000, 8, 16, 4, 2048, 2, 0, True),           # the span length in their headroom (frequent queried features)
 ])
 def test_score_and_spans_vs_oracle(H, T, k, n_feat, nq, span_len, top_b, max_freq, nms):
     rng = np.random.default_rng(H * T + k + nq + span_len)

@@ -329,6 +329,55 @@ def test_topb_hand_cases():
     assert st.tolist() == list(range(7))
 
 
+def test_preact_at_closed_forms():
+    """Sec. 3.3 encoder equation at single entries: the hand case's z table, and z = +-x_c + b for a one-hot
+    dictionary [I; -I] (the feature row picks the channel, so a transposed or shifted index cannot pass)."""
+    g = tiny()
+    x, w, b = np.array(g["x"], np.float32), np.array(g["w_enc"], np.float32), np.array(g["b_enc"], np.float32)
+    all_ids = np.broadcast_to(np.arange(8, dtype=np.int32)[::-1], (6, 8))            # every feature, in reversed order
+    assert np.array_equal(orc.preact_at(x, w, b, all_ids, "fp32"), np.array(g["z"], np.float64)[:, ::-1])
+    rng = np.random.default_rng(21)
+    d, T = 16, 9
+    xb = synth.to_storage(rng.standard_normal((T, d)).astype(np.float32), "bf16")
+    wb = synth.to_storage(np.concatenate([np.eye(d), -np.eye(d)]).astype(np.float32), "bf16")
+    bias = rng.standard_normal(2 * d).astype(np.float32)
+    ids = rng.integers(0, 2 * d, (T, 5)).astype(np.int32)
+    xf = synth.storage_to_f64(xb, "bf16")
+    want = np.where(ids < d, 1.0, -1.0) * np.take_along_axis(xf, ids % d, axis=1) + bias[ids].astype(np.float64)
+    assert np.array_equal(orc.preact_at(xb, wb, bias, ids, "bf16"), want)
+    with pytest.raises(ValueError):
+        orc.preact_at(xb, wb, bias, np.full((T, 1), 2 * d, np.int32), "bf16")
+
+
+def test_score_dense_hand_case_and_set_intersection():
+    """The token-wise form of the scoring equation against things other than the oracle: the hand-computed case
+    (scores in units of IDF(3)), and App. D.2's set-intersection sum written out with Python sets, for several
+    heads, duplicate query pairs, a zero activation and the strict freq > max_freq rule."""
+    g = tiny()
+    ids = np.array(g["ids"], np.int32)[None]
+    S = orc.score_dense(ids, np.array(g["qids"], np.int32)[None], np.array(g["qvals"], np.float32)[None], 8)
+    assert np.allclose(S, np.array(g["S_in_idf3_units"]) * g["idf3"], rtol=1e-15)
+    rng = np.random.default_rng(13)
+    H, L, k, n_feat, nq = 2, 120, 4, 30, 6
+    ids = np.stack([np.stack([rng.choice(n_feat, k, replace=False) for _ in range(L)]) for _ in range(H)]).astype(np.int32)
+    qids = np.stack([np.stack([rng.choice(n_feat, k, replace=False) for _ in range(nq)]) for _ in range(H)]).astype(np.int32)
+    qids[:, -1] = qids[:, 0]
+    qvals = rng.random((H, nq, k)).astype(np.float32)
+    qvals[0, 0, 0] = 0.0
+    freq = [np.bincount(ids[h].ravel(), minlength=n_feat) for h in range(H)]
+    for max_freq in (0, int(np.median(freq[0]))):
+        want = np.zeros(L)
+        for h in range(H):
+            for t in range(L):
+                Ft = set(ids[h, t].tolist())
+                for q in range(nq):
+                    for j in range(k):
+                        f = int(qids[h, q, j])
+                        if f in Ft and not (max_freq > 0 and freq[h][f] > max_freq):
+                            want[t] += float(qvals[h, q, j]) / (math.log(1 + freq[h][f]) + 1)
+        assert np.allclose(orc.score_dense(ids, qids, qvals, n_feat, max_freq=max_freq), want, rtol=1e-12, atol=0)
+
+
 def test_score_dense_equals_postings_form():
     """The token-wise evaluation of the scoring equation (Sec. 3.5) and the postings traversal are the same sum."""
     rng = np.random.default_rng(11)
