@@ -141,6 +141,18 @@ int s3_index_build(const int32_t* ids, const int32_t* positions, int T, int k, i
                    int32_t* offsets, int32_t* out_positions, void* ws, size_t ws_bytes,
                    void* stream);
 
+/* s3_index_build for callers that cannot allocate and have no workspace to pass: code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, results and
+ * errors as s3_index_build without ws / ws_bytes: the workspace is a buffer of
+ * S3_STATIC_SCRATCH_BYTES that is built into the library (static device memory, one copy per GPU,
+ * held until the process ends).  The call allocates nothing, frees nothing and records no memset.
+ * S3_ECAPACITY when s3_index_build_workspace(T, k, n_feat) exceeds S3_STATIC_SCRATCH_BYTES
+ * (about T * k <= 4 M postings).  All calls on one GPU share the buffer: calls that overlap on
+ * that GPU (different streams, or threads on different streams) race; serialise them. */
+#define S3_STATIC_SCRATCH_BYTES (16u << 20)
+int s3_index_build_static(const int32_t* ids, const int32_t* positions, int T, int k, int n_feat,
+                          int32_t* offsets, int32_t* out_positions, void* stream);
+
 /* ------------------------------------------------------------------------------------------
  * Sec. 3.5 scoring equation with App. D.2's weights:
  *     S[t] = sum over heads h, over query pairs (q, j) with f = qids[h, q, j]:

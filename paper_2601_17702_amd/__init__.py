@@ -52,6 +52,8 @@ def lib():
         L.s3_index_build_workspace.argtypes = [ci, ci, ci]
         L.s3_index_build_workspace.restype = sz
         L.s3_index_build.argtypes = [vp, vp, ci, ci, ci, vp, vp, vp, sz, vp]
+        L.s3_index_build_static.argtypes = [vp, vp, ci, ci, ci, vp, vp, vp]
+        L.s3_index_build_static.restype = ci
         L.s3_coactivate_score_workspace.argtypes = [vp, i64]
         L.s3_coactivate_score_workspace.restype = sz
         L.s3_coactivate_score.argtypes = [vp, vp, vp, ci, i64, ci, ci, i32, ci, vp, vp, vp, vp, vp, sz, vp]
@@ -231,4 +233,18 @@ def index_build(ids, n_feat: int, positions=None):
     pos = torch.empty(T * k, dtype=torch.int32, device=ids.device)
     _check(lib().s3_index_build(_ptr(ids), _ptr(positions), T, k, n_feat, _ptr(off), _ptr(pos), _ptr(ws),
                                 ws.numel(), _stream()))
+    return off, pos
+
+
+STATIC_SCRATCH_BYTES = 16 << 20
+
+
+def index_build_static(ids, n_feat: int, off, pos, positions=None):
+    """s3_index_build_static: one-shot CSR into the caller's off [n_feat + 1] / pos [T * k]; allocates nothing."""
+    import torch
+    assert ids.is_cuda and ids.is_contiguous() and ids.dtype == torch.int32 and ids.dim() == 2
+    T, k = ids.shape
+    assert off.is_cuda and off.dtype == torch.int32 and off.numel() >= n_feat + 1 and off.is_contiguous()
+    assert pos.is_cuda and pos.dtype == torch.int32 and pos.numel() >= T * k and pos.is_contiguous()
+    _check(lib().s3_index_build_static(_ptr(ids), _ptr(positions), T, k, n_feat, _ptr(off), _ptr(pos), _stream()))
     return off, pos

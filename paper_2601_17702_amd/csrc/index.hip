@@ -419,6 +419,82 @@ void s3_index_view(const s3_index* idx, int* n_heads, int* n_feat, int* k, int64
     *positions = idx->d.positions; *pos_stride = idx->d.pos_stride; *finalized = idx->finalized;
 }
 
+// Workspace of the one-shot build: inter | piece | total | bbase | pos_log
+static size_t build_layout(int T, int k, int n_feat, const Geometry& g, size_t off[5]) {
+    int max_tiles = (T + g.ptok - 1) / g.ptok;
+    if (max_tiles < 1) max_tiles = 1;
+    size_t o = 0;
+    auto take = [&](size_t bytes) { size_t at = o; o += s3_align(bytes); return at; };
+    off[0] = take((size_t)max_tiles * g.tile_post * 4);
+    off[1] = take((size_t)g.NB * max_tiles * 4);
+    off[2] = take((size_t)g.NB * 4);
+    off[3] = take((size_t)(g.NB + 1) * 4);
+    off[4] = take((size_t)(T > 0 ? T : 1) * 4);
+    return o;
+}
+
+__global__ void idx_fill_kernel(int32_t* dst, int n, int32_t v) {
+    int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) dst[i] = v;
+}
+
+static int index_build_impl(const char* who, const int32_t* ids, const int32_t* positions, int T, int k, int n_feat,
+                            int32_t* offsets, int32_t* out_positions, void* ws, size_t ws_bytes, void* stream) {
+    Geometry g;
+    if (T < 0 || !geometry(n_feat, k, g)) return s3_fail(S3_EINVAL, "%s: T %d, n_feat %d, k %d out of range", who, T, n_feat, k);
+    if (!offsets || (T > 0 && (!ids || !out_positions || !ws))) return s3_fail(S3_EINVAL, "%s: null pointer", who);
+    if (T > (1 << 24) || (int64_t)T * k >= (1LL << 31)) return s3_fail(S3_EINVAL, "%s: T %d too large", who, T);
+    size_t off[5];
+    size_t need = build_layout(T, k, n_feat, g, off);
+    if (T > 0 && ws_bytes < need) return s3_fail(S3_ECAPACITY, "%s: workspace %zu < %zu bytes", who, ws_bytes, need);
+    if (T > 0 && ((uintptr_t)ws & 255)) return s3_fail(S3_EINVAL, "%s: workspace must be 256-byte aligned", who);
+    hipStream_t st = (hipStream_t)stream;
+    if (T == 0) {      // an empty index: every list is empty (a fill kernel, so that a caller may capture the call in a graph)
+        hipLaunchKernelGGL(idx_fill_kernel, dim3((n_feat + 1 + 255) / 256), dim3(256), 0, st, offsets, n_feat + 1, 0);
+        S3_HIP(hipGetLastError());
+        return S3_OK;
+    }
+    char* base = (char*)ws;
+    IdxDev d;
+    d.n_feat = n_feat; d.k = k; d.S = g.S; d.NB = g.NB; d.nbB = g.nbB; d.ptok = g.ptok; d.tile_post = g.tile_post;
+    d.kinv = k > 1 ? (uint32_t)(((1ull << 32) + (uint32_t)k - 1) / (uint32_t)k) : 0u;
+    d.max_tiles = (T + g.ptok - 1) / g.ptok;
+    d.inter = (uint32_t*)(base + off[0]); d.piece = (uint32_t*)(base + off[1]);
+    d.total = (int32_t*)(base + off[2]); d.bbase = (int32_t*)(base + off[3]);
+    int32_t* plog = (int32_t*)(base + off[4]);
+    d.pos_log = plog; d.offsets = offsets; d.positions = out_positions;
+    d.inter_stride = 0; d.piece_stride = 0; d.off_stride = 0; d.pos_stride = 0;
+    if (positions) {
+        S3_HIP(hipMemcpyAsync(plog, positions, (size_t)T * 4, hipMemcpyDeviceToDevice, st));
+    } else {
+        hipLaunchKernelGGL(idx_fill_positions_kernel, dim3((T + 255) / 256), dim3(256), 0, st, plog, T, 0);
+    }
+    int rc = run_partition(ids, 0, T, 0, 1, d, st);
+    if (rc) return rc;
+    return run_finalize(d, 1, d.max_tiles, st);
+}
+
+// Scratch of s3_index_build_static: one array per GPU the library runs on, held until the process ends.  The name
+// below is a host-side stand-in; the array's device address is looked up once per device and used from then on.
+static __device__ __align__(256) unsigned char scratch[S3_STATIC_SCRATCH_BYTES];
+
+static int static_scratch(void** out) {
+    static std::mutex mu;
+    static void* ptr[kS3MaxDevices] = {};
+    int dev = 0;
+    S3_HIP(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kS3MaxDevices) return s3_fail(S3_EINVAL, "s3_index_build_static: device %d not supported", dev);
+    std::lock_guard<std::mutex> lock(mu);
+    if (!ptr[dev]) {
+        void* p = nullptr;
+        S3_HIP(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+        if (!p) return s3_fail(S3_EHIP, "s3_index_build_static: hipGetSymbolAddress returned a null address");
+        ptr[dev] = p;
+    }
+    *out = ptr[dev];
+    return S3_OK;
+}
+
 extern "C" {
 
 int s3_index_create(int n_heads, int n_feat, int k, int64_t max_tokens, s3_index** out) {
@@ -572,20 +648,6 @@ int s3_index_export(const s3_index* idx, int head, int32_t* offsets_out, int32_t
     return S3_OK;
 }
 
-// Workspace of the one-shot build: inter | piece | total | bbase | pos_log
-static size_t build_layout(int T, int k, int n_feat, const Geometry& g, size_t off[5]) {
-    int max_tiles = (T + g.ptok - 1) / g.ptok;
-    if (max_tiles < 1) max_tiles = 1;
-    size_t o = 0;
-    auto take = [&](size_t bytes) { size_t at = o; o += s3_align(bytes); return at; };
-    off[0] = take((size_t)max_tiles * g.tile_post * 4);
-    off[1] = take((size_t)g.NB * max_tiles * 4);
-    off[2] = take((size_t)g.NB * 4);
-    off[3] = take((size_t)(g.NB + 1) * 4);
-    off[4] = take((size_t)(T > 0 ? T : 1) * 4);
-    return o;
-}
-
 size_t s3_index_build_workspace(int T, int k, int n_feat) {
     Geometry g;
     if (T < 0 || !geometry(n_feat, k, g)) return 0;
@@ -595,38 +657,23 @@ size_t s3_index_build_workspace(int T, int k, int n_feat) {
 
 int s3_index_build(const int32_t* ids, const int32_t* positions, int T, int k, int n_feat, int32_t* offsets,
                    int32_t* out_positions, void* ws, size_t ws_bytes, void* stream) {
+    return index_build_impl("s3_index_build", ids, positions, T, k, n_feat, offsets, out_positions, ws, ws_bytes, stream);
+}
+
+int s3_index_build_static(const int32_t* ids, const int32_t* positions, int T, int k, int n_feat, int32_t* offsets,
+                          int32_t* out_positions, void* stream) {
     Geometry g;
     if (T < 0 || !geometry(n_feat, k, g))
-        return s3_fail(S3_EINVAL, "s3_index_build: T %d, n_feat %d, k %d out of range", T, n_feat, k);
-    if (!offsets || (T > 0 && (!ids || !out_positions || !ws))) return s3_fail(S3_EINVAL, "s3_index_build: null pointer");
-    if (T > (1 << 24) || (int64_t)T * k >= (1LL << 31)) return s3_fail(S3_EINVAL, "s3_index_build: T %d too large", T);
+        return s3_fail(S3_EINVAL, "s3_index_build_static: T %d, n_feat %d, k %d out of range", T, n_feat, k);
     size_t off[5];
-    size_t need = build_layout(T, k, n_feat, g, off);
-    if (T > 0 && ws_bytes < need) return s3_fail(S3_ECAPACITY, "s3_index_build: workspace %zu < %zu bytes", ws_bytes, need);
-    if (T > 0 && ((uintptr_t)ws & 255)) return s3_fail(S3_EINVAL, "s3_index_build: workspace must be 256-byte aligned");
-    hipStream_t st = (hipStream_t)stream;
-    if (T == 0) {
-        S3_HIP(hipMemsetAsync(offsets, 0, (size_t)(n_feat + 1) * 4, st));
-        return S3_OK;
-    }
-    char* base = (char*)ws;
-    IdxDev d;
-    d.n_feat = n_feat; d.k = k; d.S = g.S; d.NB = g.NB; d.nbB = g.nbB; d.ptok = g.ptok; d.tile_post = g.tile_post;
-    d.kinv = k > 1 ? (uint32_t)(((1ull << 32) + (uint32_t)k - 1) / (uint32_t)k) : 0u;
-    d.max_tiles = (T + g.ptok - 1) / g.ptok;
-    d.inter = (uint32_t*)(base + off[0]); d.piece = (uint32_t*)(base + off[1]);
-    d.total = (int32_t*)(base + off[2]); d.bbase = (int32_t*)(base + off[3]);
-    int32_t* plog = (int32_t*)(base + off[4]);
-    d.pos_log = plog; d.offsets = offsets; d.positions = out_positions;
-    d.inter_stride = 0; d.piece_stride = 0; d.off_stride = 0; d.pos_stride = 0;
-    if (positions) {
-        S3_HIP(hipMemcpyAsync(plog, positions, (size_t)T * 4, hipMemcpyDeviceToDevice, st));
-    } else {
-        hipLaunchKernelGGL(idx_fill_positions_kernel, dim3((T + 255) / 256), dim3(256), 0, st, plog, T, 0);
-    }
-    int rc = run_partition(ids, 0, T, 0, 1, d, st);
-    if (rc) return rc;
-    return run_finalize(d, 1, d.max_tiles, st);
+    const size_t need = build_layout(T, k, n_feat, g, off);
+    if (need > S3_STATIC_SCRATCH_BYTES)
+        return s3_fail(S3_ECAPACITY, "s3_index_build_static: T %d x k %d needs %zu bytes of scratch, the built-in buffer has %zu",
+                       T, k, need, (size_t)S3_STATIC_SCRATCH_BYTES);
+    void* ws = nullptr;
+    if (int rc = static_scratch(&ws)) return rc;
+    return index_build_impl("s3_index_build_static", ids, positions, T, k, n_feat, offsets, out_positions, ws,
+                            S3_STATIC_SCRATCH_BYTES, stream);
 }
 
 }  // extern "C"
