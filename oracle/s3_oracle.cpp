@@ -4,7 +4,9 @@
 // against the paper by eye.  It shares no code with the HIP library and is loaded only by the
 // tests, by the smoke check and by the benchmark's cpu_baseline leg; the product path never
 // calls it.  Every function below is pinned by CPU tests against closed forms, hand-computed
-// cases, brute force and library routines (no function here is "parity unpinned").
+// cases, brute force and library routines (no function here is "parity unpinned").  Where the
+// paper leaves a step open (the smoothing weights, the suppression rule, how a span grows), the
+// reading taken is stated at the function.
 //
 // All pointers are host pointers.  bf16 inputs arrive as uint16 bit patterns and are widened
 // exactly; nothing is rounded before the fp64 arithmetic.
@@ -205,6 +207,95 @@ int orc_topb(const double* W, int64_t nw, int span_len, int top_b, int nms, int3
         }
     }
     return found;
+}
+
+// ---- the rest of Phase 2 and the set operations of Phase 3 (Sec. 3.5 "Adaptive Granularity", Sec. 3.6, Alg. 1) ----
+
+// Smoothing kernels for the density curve.  The paper fixes only the sizes (App. B.3: 48, 8 for QA), not the
+// weights; three shapes are offered, each normalised to sum 1 so that the curve stays in the units of S:
+// kind 0 box (1/K each), 1 triangular (w_j proportional to min(j + 1, K - j)), 2 Gaussian centred at (K - 1) / 2
+// with sigma = K / 6.
+int orc_smoothing_kernel(int kind, int K, double* g) {
+    if (K < 1 || kind < 0 || kind > 2) return -1;
+    double sum = 0.0;
+    for (int j = 0; j < K; ++j) {
+        double v = 1.0;
+        if (kind == 1) v = (double)std::min(j + 1, K - j);
+        if (kind == 2) {
+            const double u = ((double)j - 0.5 * (K - 1)) / ((double)K / 6.0);
+            v = std::exp(-0.5 * u * u);
+        }
+        g[j] = v;
+        sum += v;
+    }
+    for (int j = 0; j < K; ++j) g[j] /= sum;
+    return 0;
+}
+
+// Alg. 1 Phase 2, S' <- Conv1D(S): D[t] = sum_j g[j] * S[t + j - floor(K / 2)], same length as S, zeros outside
+// (tap floor(K / 2) sits on t; cross-correlation form, which equals convolution for the symmetric kernels above).
+int orc_conv1d(const double* S, int64_t L, const double* g, int K, double* D) {
+    if (L < 0 || K < 1) return -1;
+    const int64_t c = K / 2;
+    for (int64_t t = 0; t < L; ++t) {
+        double acc = 0.0;
+        for (int j = 0; j < K; ++j) {
+            const int64_t u = t + j - c;
+            if (u >= 0 && u < L) acc += g[j] * S[u];
+        }
+        D[t] = acc;
+    }
+    return 0;
+}
+
+// Alg. 1 Phase 2, NMS_Select(S', N): density peaks by greedy non-maximum suppression.  Repeat up to n_centers
+// times: the largest remaining density (ties -> smallest position) becomes a centre if it is positive; every
+// position within `radius` of it is suppressed.  Returns the number of centres.
+int orc_nms_peaks(const double* D, int64_t L, int n_centers, int radius, int32_t* centers, double* peak) {
+    std::vector<char> dead(L, 0);
+    int found = 0;
+    for (int r = 0; r < n_centers; ++r) {
+        int64_t best = -1;
+        for (int64_t t = 0; t < L; ++t)
+            if (!dead[t] && (best < 0 || D[t] > D[best])) best = t;
+        if (best < 0 || !(D[best] > 0.0)) break;
+        centers[found] = (int32_t)best;
+        peak[found] = D[best];
+        ++found;
+        for (int64_t t = std::max<int64_t>(0, best - radius); t <= std::min<int64_t>(L - 1, best + radius); ++t) dead[t] = 1;
+    }
+    return found;
+}
+
+// Sec. 3.5: "for each peak, we retrieve a variable-length span", read as the region around the centre where the
+// density stays at or above rel * D[centre] (the cut falls where the evidence thins out), at most max_half
+// positions to either side: lo and hi are inclusive.
+void orc_grow_span(const double* D, int64_t L, int32_t c, double rel, int max_half, int32_t* lo, int32_t* hi) {
+    const double thr = rel * D[c];
+    int64_t a = c, b = c;
+    while (a - 1 >= 0 && c - (a - 1) <= max_half && D[a - 1] >= thr) --a;
+    while (b + 1 < L && (b + 1) - c <= max_half && D[b + 1] >= thr) ++b;
+    *lo = (int32_t)a;
+    *hi = (int32_t)b;
+}
+
+// Sec. 3.6 / Alg. 1 Phase 3: Idx_final = Idx_S3 U Idx_lexical U LeadTail as a set of positions: the union of the
+// spans [lo_i, hi_i], of an externally supplied index list (positions outside [0, L) are ignored) and of the first
+// `lead` and last `tail` positions.  mask [L] gets 0 / 1; idx gets the selected positions in ascending order.
+// Returns their number.
+int64_t orc_fuse(int64_t L, const int32_t* lo, const int32_t* hi, int n_spans, const int32_t* extra, int64_t n_extra,
+                 int lead, int tail, unsigned char* mask, int32_t* idx) {
+    for (int64_t t = 0; t < L; ++t) mask[t] = 0;
+    for (int i = 0; i < n_spans; ++i)
+        for (int64_t t = std::max<int64_t>(lo[i], 0); t <= std::min<int64_t>(hi[i], L - 1); ++t) mask[t] = 1;
+    for (int64_t i = 0; i < n_extra; ++i)
+        if (extra[i] >= 0 && extra[i] < L) mask[extra[i]] = 1;
+    for (int64_t t = 0; t < std::min<int64_t>(lead, L); ++t) mask[t] = 1;
+    for (int64_t t = std::max<int64_t>(0, L - tail); t < L; ++t) mask[t] = 1;
+    int64_t n = 0;
+    for (int64_t t = 0; t < L; ++t)
+        if (mask[t]) idx[n++] = (int32_t)t;
+    return n;
 }
 
 // Number of host threads orc_encode_topk uses (rows are independent; nothing else is threaded).

@@ -50,6 +50,13 @@ def lib():
         L.orc_pool.restype = i64
         L.orc_topb.argtypes = [vp, i64, C.c_int, C.c_int, C.c_int, vp, vp]
         L.orc_threads.restype = C.c_int
+        L.orc_smoothing_kernel.argtypes = [C.c_int, C.c_int, vp]
+        L.orc_conv1d.argtypes = [vp, i64, vp, C.c_int, vp]
+        L.orc_nms_peaks.argtypes = [vp, i64, C.c_int, C.c_int, vp, vp]
+        L.orc_grow_span.argtypes = [vp, i64, i32, C.c_double, C.c_int, vp, vp]
+        L.orc_grow_span.restype = None
+        L.orc_fuse.argtypes = [i64, vp, vp, C.c_int, vp, i64, C.c_int, C.c_int, vp, vp]
+        L.orc_fuse.restype = i64
         _lib = L
     return _lib
 
@@ -160,6 +167,53 @@ def topb(W, span_len, top_b, nms=True):
     scores = np.empty(top_b, np.float64)
     n = lib().orc_topb(_p(W), W.shape[0], int(span_len), int(top_b), int(bool(nms)), _p(starts), _p(scores))
     return starts[:n].copy(), scores[:n].copy()
+
+
+KERNEL_KINDS = {"box": 0, "triangular": 1, "gaussian": 2}
+
+
+def smoothing_kernel(kind: str, K: int):
+    g = np.empty(K, np.float64)
+    if lib().orc_smoothing_kernel(KERNEL_KINDS[kind], int(K), _p(g)) != 0:
+        raise ValueError("orc_smoothing_kernel: invalid arguments")
+    return g
+
+
+def conv1d(S, g):
+    S = np.ascontiguousarray(S, dtype=np.float64)
+    g = np.ascontiguousarray(g, dtype=np.float64)
+    D = np.empty_like(S)
+    lib().orc_conv1d(_p(S), S.shape[0], _p(g), g.shape[0], _p(D))
+    return D
+
+
+def nms_peaks(D, n_centers, radius):
+    D = np.ascontiguousarray(D, dtype=np.float64)
+    c = np.empty(n_centers, np.int32)
+    v = np.empty(n_centers, np.float64)
+    n = lib().orc_nms_peaks(_p(D), D.shape[0], int(n_centers), int(radius), _p(c), _p(v))
+    return c[:n].copy(), v[:n].copy()
+
+
+def grow_spans(D, centers, rel, max_half):
+    D = np.ascontiguousarray(D, dtype=np.float64)
+    lo = np.empty(len(centers), np.int32)
+    hi = np.empty(len(centers), np.int32)
+    a, b = C.c_int32(), C.c_int32()
+    for i, c in enumerate(centers):
+        lib().orc_grow_span(_p(D), D.shape[0], int(c), float(rel), int(max_half), C.byref(a), C.byref(b))
+        lo[i], hi[i] = a.value, b.value
+    return lo, hi
+
+
+def fuse(L, lo, hi, extra, lead, tail):
+    lo = np.ascontiguousarray(lo, dtype=np.int32)
+    hi = np.ascontiguousarray(hi, dtype=np.int32)
+    extra = np.ascontiguousarray(extra, dtype=np.int32)
+    mask = np.empty(L, np.uint8)
+    idx = np.empty(max(L, 1), np.int32)
+    n = lib().orc_fuse(int(L), _p(lo), _p(hi), len(lo), _p(extra), extra.shape[0], int(lead), int(tail), _p(mask), _p(idx))
+    return mask, idx[:n].copy()
 
 
 def threads() -> int:

@@ -90,6 +90,21 @@ static int random_shapes() {
             const int found = orc_topb(W.data(), nw, len, (int)nw + 2, 1, st.data(), sc.data());
             CHECK(found >= 1 && found <= nw);
         }
+        // Phase-2 tail and Phase-3 set operations on the same scores
+        for (int K : {1, 8, 48}) {
+            std::vector<double> g(K), D(L);
+            CHECK(orc_smoothing_kernel(K % 3, K, g.data()) == 0);
+            CHECK(orc_conv1d(S.data(), L, g.data(), K, D.data()) == 0);
+            std::vector<int32_t> c(40), lo(40), hi(40);
+            std::vector<double> pk(40);
+            const int n = orc_nms_peaks(D.data(), L, 40, K / 2, c.data(), pk.data());
+            for (int i = 0; i < n; ++i) orc_grow_span(D.data(), L, c[i], 0.5, 24, &lo[i], &hi[i]);
+            std::vector<unsigned char> mask(L);
+            std::vector<int32_t> idx(L);
+            const int32_t extra[3] = {-1, 0, (int32_t)L + 4};
+            const int64_t m = orc_fuse(L, lo.data(), hi.data(), n, extra, 3, 4, 4, mask.data(), idx.data());
+            CHECK(m >= 1 && m <= L);
+        }
         orc_index_free(ix);
     }
     return 0;
