@@ -14,12 +14,15 @@
 //              LDS by the low feature bits (stable again) and written to their final place in the
 //              CSR; the per-feature counts of the bucket give offsets[].
 //
-// Both splits are one pass of a ballot-based multi-way split: the lanes of a wavefront that hold the same
+// The bucket pass is one pass of a ballot-based multi-way split: the lanes of a wavefront that hold the same
 // digit find each other with one ballot per digit bit, per-wavefront counters and one block-wide prefix sum
-// give every entry its rank.
+// give every entry its rank.  The append pass ranks with one returning LDS add per token row instead (a token's
+// ids are distinct, so the entries of one feature are always in different rows and keep their order); for very
+// small k it uses the ballots too.
 //
-// All ranks come from prefix sums over fixed lane and wavefront orders: no atomics decide a position, so the
-// CSR is bit-identical from run to run and independent of how the stream was chunked.
+// The order of the entries of ONE feature is fixed by prefix sums over lane, row and wavefront orders: the CSR is
+// bit-identical from run to run and independent of how the stream was chunked.  (Inside a tile of the intermediate
+// array, entries of different features that share a bucket and a token may come in either order.)
 #include "s3_common.h"
 
 #include <new>
@@ -36,9 +39,13 @@ struct IdxDev {
     int32_t* bbase;       // [n_heads][NB + 1]
     int32_t* offsets;     // [n_heads][n_feat + 1]  (stride off_stride)
     int32_t* positions;   // [n_heads][pos_stride]
-    const int32_t* pos_log;   // [max_tokens] absolute position of each appended row
+    const int32_t* pos_log;   // [max_tokens] absolute position of each appended row (read unless pos_affine)
+    int32_t* btab;            // [n_heads][n_feat][nblk - 1] block table for scoring, or null
     int64_t inter_stride, piece_stride, off_stride, pos_stride;
     int n_feat, k, S, NB, nbB, ptok, tile_post, max_tiles;
+    int nblk;                 // position blocks the table covers
+    int pos_affine;           // position of row r is pos0 + r (every append used contiguous implicit positions)
+    int32_t pos0;
     uint32_t kinv;        // ceil(2^32 / k) for k > 1: i / k == umulhi(i, kinv) for every posting index of a tile
 };
 
@@ -55,6 +62,7 @@ constexpr int kSplitWaves = kSplitThreads / 64;
 constexpr int kSplitRounds = 8;          // 16 wavefronts x 8 rounds x 64 lanes = 8192 entries per pass
 constexpr int kSplitOcc = 8;             // wavefronts per SIMD the kernels are built for: two workgroups per compute unit
 constexpr unsigned kSplitValid = 1u << 31;
+constexpr int kRowAtomicMinK = 8;        // Top-k sizes from which the append ranks a round row by row (at most 9 rows)
 
 // One round for this lane's entry with digit `dg` (low NBITS bits, the rest 0; 0 on an invalid lane).  Returns
 // dg | rank inside the wavefront << 8 | kSplitValid, or 0 for an invalid lane.
@@ -159,7 +167,20 @@ __global__ __launch_bounds__(kSplitThreads, kSplitOcc) void idx_partition_kernel
         const uint32_t dg = min(id >> d.S, (uint32_t)(nd - 1));   // ids are < n_feat by contract; never index past the counters
         const uint32_t trow = __umulhi(i, d.kinv) + i * k_is_1;   // i / k (kinv is 0 when k == 1)
         word[r] = ((row0 + trow) << d.S) | (id & mask);
-        meta[r] = split_round<8>(row, dg, valid);
+        if (d.k >= kRowAtomicMinK) {
+            // A token's ids are distinct, so entries of one feature never share a row: one returning LDS add per row
+            // of the round (in row order; a wavefront's LDS operations execute in program order) ranks every entry
+            // behind the earlier entries of its bucket in this wavefront.  Entries of different features in one
+            // row get their ranks in any order, which no posting list can see.
+            const uint32_t first = __builtin_amdgcn_readfirstlane(__umulhi(i - lane, d.kinv));
+            const uint32_t last = __builtin_amdgcn_readfirstlane(__umulhi(i - lane + 63u, d.kinv));
+            unsigned res = 0u;
+            for (uint32_t rr = first; rr <= last; ++rr)
+                if (valid && trow == rr) res = dg | ((unsigned)atomicAdd(&row[dg], 1) << 8) | kSplitValid;
+            meta[r] = res;
+        } else {
+            meta[r] = split_round<8>(row, dg, valid);
+        }
     }
     __syncthreads();
     split_scan(cnt, nd, bstart, bcount, wsum);
@@ -216,9 +237,12 @@ __global__ __launch_bounds__(kSplitThreads, kSplitOcc) void idx_bucket_sort_kern
     int* rcount = hist;                            //       per-round counts afterwards
     int* cursor = hist + 256;                      // [256]
     int* rstart = cursor + 256;                    // [256]
-    int* cnt = rstart + 256;                       // [kSplitWaves << S]
+    int* lstart = rstart + 256;                    // [256] where each list starts in the head's positions array
+    int* nextj = lstart + 256;                     // [256] first block whose start in the list is not known yet
+    int* cnt = nextj + 256;                        // [kSplitWaves << S]
 
-    const int tid = threadIdx.x, lane = tid & 63, b = blockIdx.x, head = blockIdx.y;
+    const int tid = threadIdx.x, lane = tid & 63, head = blockIdx.y;
+    const int b = blockIdx.x;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     // the first round's piece words are requested together with the bucket's totals: one memory latency, not two
     const uint32_t* pc = d.piece + (size_t)head * d.piece_stride + (size_t)b * d.max_tiles;
@@ -229,14 +253,20 @@ __global__ __launch_bounds__(kSplitThreads, kSplitOcc) void idx_bucket_sort_kern
     const int nfl = min(nd, d.n_feat - (b << d.S));
     const uint32_t mask = (1u << d.S) - 1u;
     int32_t* offs = d.offsets + (size_t)head * d.off_stride + ((size_t)b << d.S);
+    const int nbk = d.btab ? d.nblk - 1 : 0;      // block-table entries per list
+    int32_t* tab = d.btab ? d.btab + ((size_t)head * d.n_feat + ((size_t)b << d.S)) * nbk : nullptr;
     if (n_b == 0) {
-        if (tid < nfl) offs[tid] = out_base;
+        if (tid < nfl) {
+            offs[tid] = out_base;
+            for (int j = 0; j < nbk; ++j) tab[tid * nbk + j] = out_base;
+        }
         return;
     }
     const uint32_t* inter = d.inter + (size_t)head * d.inter_stride;
     int32_t* posout = d.positions + (size_t)head * d.pos_stride;
     const bool multi = n_b > kSortCap || n_tiles > kSplitThreads;   // more than one round of pieces
 
+    if (tid < 256) nextj[tid] = 1;
     if (multi) {   // count the whole bucket first: the CSR offsets are needed before the first round is written
         if (tid < 256) hist[tid] = 0;
         __syncthreads();
@@ -249,7 +279,7 @@ __global__ __launch_bounds__(kSplitThreads, kSplitOcc) void idx_bucket_sort_kern
         __syncthreads();
         int tot;
         int ex = s3_block_excl_scan<kSplitThreads>(tid < nd ? hist[tid] : 0, wsum, tot);
-        if (tid < nd) cursor[tid] = out_base + ex;
+        if (tid < nd) cursor[tid] = lstart[tid] = out_base + ex;
         if (tid < nfl) offs[tid] = out_base + ex;
         __syncthreads();
     }
@@ -308,7 +338,8 @@ __global__ __launch_bounds__(kSplitThreads, kSplitOcc) void idx_bucket_sort_kern
             const int i = wave * seg + r * 64 + lane;
             const uint32_t e = (r * 64 < seg && i < n_r) ? bufa[i] : 0u;
             meta[r] = e;
-            pos[r] = d.pos_log[e >> d.S];      // all loads in flight at once; used only after the scan (row 0 if idle)
+            // all loads in flight at once; used only after the scan (row 0 if idle)
+            pos[r] = d.pos_affine ? d.pos0 + (int32_t)(e >> d.S) : d.pos_log[e >> d.S];
         }
 #pragma unroll
         for (int r = 0; r < kSplitRounds; ++r) {
@@ -327,22 +358,51 @@ __global__ __launch_bounds__(kSplitThreads, kSplitOcc) void idx_bucket_sort_kern
             for (int r = 0; r < kSplitRounds; ++r)
                 if (meta[r] & kSplitValid) {
                     const unsigned fl = meta[r] & 0xFFu;
-                    posout[cursor[fl] + (split_rank(row, meta[r]) - rstart[fl])] = pos[r];
+                    const int i = split_rank(row, meta[r]);
+                    posout[cursor[fl] + (i - rstart[fl])] = pos[r];
+                    if (nbk) bufb[i] = pos[r];
                 }
         } else {
+            if (tid < nd) lstart[tid] = out_base + rstart[tid];
 #pragma unroll
             for (int r = 0; r < kSplitRounds; ++r)
                 if (meta[r] & kSplitValid) bufb[split_rank(row, meta[r])] = pos[r];
         }
         __syncthreads();
+        if (nbk && tid < nfl && rcount[tid] > 0) {
+            // Block table, one thread per list: the round's part of the list is sorted in bufb; every block that
+            // starts at or before its last entry and whose start is not known yet starts at the first entry of the
+            // part that lies in it or beyond (binary search).  Rounds come in position order.
+            const int32_t* seg = bufb + rstart[tid];
+            const int n = rcount[tid];
+            const int last = seg[n - 1];
+            const int gbase = multi ? cursor[tid] : lstart[tid];
+            int j = nextj[tid];
+            while (j <= nbk && last >= (j << kS3PosBlockLog2)) {
+                const int key = j << kS3PosBlockLog2;
+                int lo = 0, hi = n;
+                while (lo < hi) {
+                    const int mid = (lo + hi) >> 1;
+                    if (seg[mid] < key) lo = mid + 1; else hi = mid;
+                }
+                tab[tid * nbk + j - 1] = gbase + lo;
+                ++j;
+            }
+            nextj[tid] = j;
+        }
         if (multi) {
             if (tid < nd) cursor[tid] += rcount[tid];
         } else {
+            if (tid < nd) cursor[tid] = lstart[tid] + rcount[tid];
             for (int i = tid; i < n_r; i += kSplitThreads) posout[out_base + i] = bufb[i];
         }
         tp += m;
         if (tp < n_tiles) p_next = tp + tid < n_tiles ? pc[tp + tid] : 0u;
         __syncthreads();
+    }
+    if (nbk && tid < nfl) {      // the blocks after a list's last entry start at its end; an empty list's all do
+        const int end = cursor[tid];
+        for (int j = nextj[tid]; j <= nbk; ++j) tab[tid * nbk + j - 1] = end;
     }
 }
 
@@ -352,7 +412,7 @@ __global__ void idx_fill_positions_kernel(int32_t* dst, int n, int32_t base) {
 }
 
 size_t bucket_sort_lds(int S) {
-    return (size_t)kSortCap * 4 + (kSplitThreads + 1) * 4 + kSplitThreads * 4 + 16 * 4 + 3 * 256 * 4 +
+    return (size_t)kSortCap * 4 + (kSplitThreads + 1) * 4 + kSplitThreads * 4 + 16 * 4 + 5 * 256 * 4 +
            ((size_t)kSplitWaves << S) * 4;
 }
 
@@ -402,6 +462,11 @@ struct s3_index {
     bool finalized;
     bool sorted;          // every posting list is in increasing position order (implicit, increasing positions only)
     int64_t last_pos;     // position of the last appended row (implicit positions)
+    int64_t max_pos;      // largest position appended so far (implicit positions; meaningless once !sorted)
+    bool affine;          // every append so far used implicit positions continuing the first one's: row r is at pos0 + r
+    int32_t pos0;
+    int nblk;             // position blocks covered by the block table (0: no table)
+    int32_t* btab;
     Geometry g;
     IdxDev d;
     int32_t* pos_log;
@@ -410,13 +475,13 @@ struct s3_index {
 };
 
 // Internal view for the scoring translation unit.
-void s3_index_view(const s3_index* idx, int* n_heads, int* n_feat, int* k, int64_t* tokens,
-                                const int32_t** offsets, int64_t* off_stride, const int32_t** positions,
-                                int64_t* pos_stride, bool* finalized, bool* sorted) {
-    *sorted = idx->sorted;
-    *n_heads = idx->n_heads; *n_feat = idx->n_feat; *k = idx->k; *tokens = idx->tokens;
-    *offsets = idx->d.offsets; *off_stride = idx->d.off_stride;
-    *positions = idx->d.positions; *pos_stride = idx->d.pos_stride; *finalized = idx->finalized;
+void s3_index_view(const s3_index* idx, S3IndexView* v) {
+    v->n_heads = idx->n_heads; v->n_feat = idx->n_feat; v->k = idx->k; v->tokens = idx->tokens;
+    v->offsets = idx->d.offsets; v->off_stride = idx->d.off_stride;
+    v->positions = idx->d.positions; v->pos_stride = idx->d.pos_stride;
+    v->finalized = idx->finalized; v->sorted = idx->sorted;
+    v->btab = idx->btab; v->nblk = idx->nblk;
+    v->btab_valid = idx->btab && idx->sorted && idx->max_pos < ((int64_t)idx->nblk << kS3PosBlockLog2);
 }
 
 // Workspace of the one-shot build: inter | piece | total | bbase | pos_log
@@ -464,11 +529,8 @@ static int index_build_impl(const char* who, const int32_t* ids, const int32_t* 
     int32_t* plog = (int32_t*)(base + off[4]);
     d.pos_log = plog; d.offsets = offsets; d.positions = out_positions;
     d.inter_stride = 0; d.piece_stride = 0; d.off_stride = 0; d.pos_stride = 0;
-    if (positions) {
-        S3_HIP(hipMemcpyAsync(plog, positions, (size_t)T * 4, hipMemcpyDeviceToDevice, st));
-    } else {
-        hipLaunchKernelGGL(idx_fill_positions_kernel, dim3((T + 255) / 256), dim3(256), 0, st, plog, T, 0);
-    }
+    d.btab = nullptr; d.nblk = 0; d.pos_affine = positions ? 0 : 1; d.pos0 = 0;
+    if (positions) S3_HIP(hipMemcpyAsync(plog, positions, (size_t)T * 4, hipMemcpyDeviceToDevice, st));
     int rc = run_partition(ids, 0, T, 0, 1, d, st);
     if (rc) return rc;
     return run_finalize(d, 1, d.max_tiles, st);
@@ -509,7 +571,9 @@ int s3_index_create(int n_heads, int n_feat, int k, int64_t max_tokens, s3_index
     s3_index* ix = new (std::nothrow) s3_index();
     if (!ix) return s3_fail(S3_EHIP, "s3_index_create: out of host memory");
     ix->n_heads = n_heads; ix->n_feat = n_feat; ix->k = k; ix->max_tokens = max_tokens; ix->tokens = 0;
-    ix->finalized = false; ix->sorted = true; ix->last_pos = -1; ix->g = g;
+    ix->finalized = false; ix->sorted = true; ix->last_pos = -1; ix->max_pos = -1; ix->affine = true; ix->pos0 = 0; ix->g = g;
+    const int64_t nb = (max_tokens + (1 << kS3PosBlockLog2) - 1) >> kS3PosBlockLog2;
+    ix->nblk = nb >= 2 && nb <= kS3MaxTableBlocks ? (int)nb : 0;
     IdxDev& d = ix->d;
     d.n_feat = n_feat; d.k = k; d.S = g.S; d.NB = g.NB; d.nbB = g.nbB; d.ptok = g.ptok; d.tile_post = g.tile_post;
     d.kinv = k > 1 ? (uint32_t)(((1ull << 32) + (uint32_t)k - 1) / (uint32_t)k) : 0u;
@@ -528,6 +592,7 @@ int s3_index_create(int n_heads, int n_feat, int k, int64_t max_tokens, s3_index
     size_t o_pos = take((size_t)n_heads * d.pos_stride * 4);
     size_t o_plog = take((size_t)max_tokens * 4);
     size_t o_pend = take((size_t)n_heads * g.tile_post * 4);
+    size_t o_btab = take(ix->nblk ? (size_t)n_heads * n_feat * (ix->nblk - 1) * 4 : 0);
     hipError_t e = hipMalloc(&ix->block, o);
     if (e != hipSuccess) {
         delete ix;
@@ -539,6 +604,8 @@ int s3_index_create(int n_heads, int n_feat, int k, int64_t max_tokens, s3_index
     d.offsets = (int32_t*)(base + o_offs); d.positions = (int32_t*)(base + o_pos);
     ix->pos_log = (int32_t*)(base + o_plog); d.pos_log = ix->pos_log;
     ix->pending = (int32_t*)(base + o_pend);
+    ix->btab = ix->nblk ? (int32_t*)(base + o_btab) : nullptr;
+    d.btab = ix->btab; d.nblk = ix->nblk; d.pos_affine = 0; d.pos0 = 0;
     *out = ix;
     return S3_OK;
 }
@@ -557,6 +624,9 @@ int s3_index_reset(s3_index* idx) {
     idx->finalized = false;
     idx->sorted = true;
     idx->last_pos = -1;
+    idx->max_pos = -1;
+    idx->affine = true;
+    idx->pos0 = 0;
     return S3_OK;
 }
 
@@ -573,14 +643,25 @@ int s3_index_append(s3_index* idx, const int32_t* ids, int T, const int32_t* pos
     const IdxDev& d = idx->d;
     const int k = idx->k, ptok = d.ptok, H = idx->n_heads;
     const int64_t r0 = idx->tokens;
+    // While every append continues the first one's implicit positions, row r is at pos0 + r and no position is
+    // stored.  The first append that breaks the pattern writes the positions of the rows before it, and from
+    // then on every append stores its own.
+    const bool continues = !positions && (r0 == 0 || (idx->affine && (int64_t)base_pos == (int64_t)idx->pos0 + r0));
+    if (idx->affine && !continues && r0 > 0)
+        hipLaunchKernelGGL(idx_fill_positions_kernel, dim3((unsigned)((r0 + 255) / 256)), dim3(256), 0, st, idx->pos_log,
+                           (int)r0, idx->pos0);
+    if (r0 == 0 && !positions) idx->pos0 = base_pos;
+    idx->affine = idx->affine && continues;
     if (positions) {
         idx->sorted = false;          // caller-given positions: order unknown to the host
         S3_HIP(hipMemcpyAsync(idx->pos_log + r0, positions, (size_t)T * 4, hipMemcpyDeviceToDevice, st));
     } else {
         if ((int64_t)base_pos <= idx->last_pos) idx->sorted = false;
         idx->last_pos = (int64_t)base_pos + T - 1;
-        hipLaunchKernelGGL(idx_fill_positions_kernel, dim3((T + 255) / 256), dim3(256), 0, st, idx->pos_log + r0, T,
-                           base_pos);
+        if (idx->last_pos > idx->max_pos) idx->max_pos = idx->last_pos;
+        if (!idx->affine)
+            hipLaunchKernelGGL(idx_fill_positions_kernel, dim3((T + 255) / 256), dim3(256), 0, st, idx->pos_log + r0, T,
+                               base_pos);
     }
     int done = 0;
     const int in_tile = (int)(r0 % ptok);
@@ -618,7 +699,10 @@ int s3_index_finalize(s3_index* idx, void* stream) {
         if (rc) return rc;
     }
     const int n_tiles = (int)((idx->tokens + d.ptok - 1) / d.ptok);
-    int rc = run_finalize(d, idx->n_heads, n_tiles, st);
+    IdxDev df = d;
+    df.pos_affine = idx->affine ? 1 : 0;
+    df.pos0 = idx->pos0;
+    int rc = run_finalize(df, idx->n_heads, n_tiles, st);
     if (rc) return rc;
     idx->finalized = true;
     return S3_OK;

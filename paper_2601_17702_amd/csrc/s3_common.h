@@ -35,10 +35,28 @@ static inline int s3_ceil_log2(unsigned v) {
     return b;
 }
 
+// Scoring keeps the scores of one block of 2^kS3PosBlockLog2 positions in LDS at a time; finalize records, per
+// posting list, where each block starts (the block table), so that scoring reads no posting outside its block.
+constexpr int kS3PosBlockLog2 = 14;
+constexpr int kS3MaxTableBlocks = 64;      // no table for indexes of more blocks (longer lists are searched instead)
+
 // Read-only view of an index for the scoring translation unit (defined in index.hip).
-void s3_index_view(const s3_index* idx, int* n_heads, int* n_feat, int* k, int64_t* tokens,
-                   const int32_t** offsets, int64_t* off_stride, const int32_t** positions,
-                   int64_t* pos_stride, bool* finalized, bool* sorted);
+struct S3IndexView {
+    int n_heads, n_feat, k;
+    int64_t tokens;
+    const int32_t* offsets;      // [n_heads] x off_stride
+    const int32_t* positions;    // [n_heads] x pos_stride
+    int64_t off_stride, pos_stride;
+    bool finalized;
+    bool sorted;                 // every list ascends in position (implicit, increasing positions only)
+    // block table: btab[(h * n_feat + f) * (nblk - 1) + j - 1] = index, in head h's positions array, of the first
+    // posting of list f whose position is >= j << kS3PosBlockLog2, j = 1 .. nblk - 1.  Null when there is none;
+    // valid only for sorted lists whose positions are all below nblk << kS3PosBlockLog2 (btab_valid).
+    const int32_t* btab;
+    int nblk;
+    bool btab_valid;
+};
+void s3_index_view(const s3_index* idx, S3IndexView* out);
 
 // ---- prefix sums shared by the index and the scoring kernels ----
 // Inclusive prefix sums over the lanes of a wavefront / over each row of 16 lanes, by data-parallel-primitive
