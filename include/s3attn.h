@@ -184,6 +184,51 @@ int s3_coactivate_score(const s3_index* idx, const int32_t* qids, const float* q
                         float* scores_out, int32_t* span_start, float* span_score,
                         int32_t* n_found, void* ws, size_t ws_bytes, void* stream);
 
+/* ------------------------------------------------------------------------------------------
+ * Sec. 3.5 "Adaptive Granularity" and Alg. 1 Phase 2 (S' <- Conv1D(S); Idx <- NMS_Select(S', N)) with
+ * a smoothing kernel of the caller's choice and variable-length spans.  The paper fixes the sizes
+ * (App. B.3: kernel 48, 8 for QA; N = 40 centres) and leaves the weights, the suppression rule and
+ * the span rule open; the readings taken:
+ *     D[t] = sum_{j < K} kernel[j] * S[t + j - floor(K / 2)]        (zeros outside [0, L))
+ *     repeat n_centers times: c = the remaining position of largest D (ties: smallest t); stop if
+ *         D[c] <= 0; every position within nms_radius of c is suppressed
+ *     span of c = [c - a, c + b], a and b the largest values <= max_half_len (and inside the context)
+ *         such that D >= rel_threshold * D[c] at every position of the span
+ * D is accumulated in fp64 from the fp32 inputs and rounded to fp32 once; all comparisons use
+ * those fp32 values (threshold product in fp64), so the result does not depend on execution order.
+ *
+ *   scores [n_positions] fp32 (the scores_out of s3_coactivate_score); kernel [K] fp32, device;
+ *   density_out [n_positions] fp32 or NULL; center / span_lo / span_hi [n_centers] int32,
+ *   center_density [n_centers] fp32, n_found [1] int32; entries past n_found are -1 / 0.
+ *   ws: s3_select_spans_workspace(n_positions) bytes, 256-byte aligned.
+ * Limits: 1 <= K <= 4096; 1 <= n_centers <= 4096; nms_radius, max_half_len >= 0;
+ * 0 <= rel_threshold <= 1.
+ *
+ * s3_smoothing_kernel fills a HOST array with the weights of a box (1/K each), triangular
+ * (proportional to min(j + 1, K - j)) or Gaussian (centre (K - 1) / 2, sigma K / 6) kernel, each
+ * normalised to sum 1; the caller copies them to the device. */
+enum { S3_KERNEL_BOX = 0, S3_KERNEL_TRIANGULAR = 1, S3_KERNEL_GAUSSIAN = 2 };
+int s3_smoothing_kernel(int kind, int K, float* weights);
+size_t s3_select_spans_workspace(int64_t n_positions);
+int s3_select_spans(const float* scores, int64_t n_positions, const float* kernel, int K, int n_centers,
+                    int nms_radius, float rel_threshold, int max_half_len, float* density_out,
+                    int32_t* center, float* center_density, int32_t* span_lo, int32_t* span_hi,
+                    int32_t* n_found, void* ws, size_t ws_bytes, void* stream);
+
+/* Sec. 3.6 / Alg. 1 Phase 3, Idx_final = Idx_S3 U Idx_lexical U LeadTail, as a set of positions:
+ * the union of the spans [span_lo[i], span_hi[i]] (inclusive; i < min(*n_spans, max_spans), n_spans a
+ * device pointer or NULL for max_spans), of the caller's index list `extra` (the lexical retriever's
+ * output; entries outside [0, n_positions) are ignored, repeats are fine) and of the first `lead`
+ * and last `tail` positions.
+ *   mask [n_positions] uint8 (0 / 1); idx_out [n_positions] int32: the selected positions in
+ *   ascending order; n_out [1] int32 their number.  ws: s3_fuse_indices_workspace(n_positions) bytes.
+ * Limits: max_spans <= 65535; n_extra < 2^31. */
+size_t s3_fuse_indices_workspace(int64_t n_positions);
+int s3_fuse_indices(int64_t n_positions, const int32_t* span_lo, const int32_t* span_hi,
+                    const int32_t* n_spans, int max_spans, const int32_t* extra, int64_t n_extra,
+                    int lead, int tail, unsigned char* mask, int32_t* idx_out, int32_t* n_out, void* ws,
+                    size_t ws_bytes, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

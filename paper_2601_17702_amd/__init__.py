@@ -57,6 +57,16 @@ def lib():
         L.s3_coactivate_score_workspace.argtypes = [vp, i64]
         L.s3_coactivate_score_workspace.restype = sz
         L.s3_coactivate_score.argtypes = [vp, vp, vp, ci, i64, ci, ci, i32, ci, vp, vp, vp, vp, vp, sz, vp]
+        L.s3_smoothing_kernel.argtypes = [ci, ci, vp]
+        L.s3_smoothing_kernel.restype = ci
+        L.s3_select_spans_workspace.argtypes = [i64]
+        L.s3_select_spans_workspace.restype = sz
+        L.s3_select_spans.argtypes = [vp, i64, vp, ci, ci, ci, C.c_float, ci, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.s3_select_spans.restype = ci
+        L.s3_fuse_indices_workspace.argtypes = [i64]
+        L.s3_fuse_indices_workspace.restype = sz
+        L.s3_fuse_indices.argtypes = [i64, vp, vp, vp, ci, vp, i64, ci, ci, vp, vp, vp, vp, sz, vp]
+        L.s3_fuse_indices.restype = ci
         for name in ("s3_sae_encode_topk", "s3_sae_encode_topk_stream", "s3_index_create", "s3_index_append", "s3_index_finalize",
                      "s3_index_csr", "s3_index_build", "s3_coactivate_score"):
             getattr(L, name).restype = ci
@@ -248,3 +258,52 @@ def index_build_static(ids, n_feat: int, off, pos, positions=None):
     assert pos.is_cuda and pos.dtype == torch.int32 and pos.numel() >= T * k and pos.is_contiguous()
     _check(lib().s3_index_build_static(_ptr(ids), _ptr(positions), T, k, n_feat, _ptr(off), _ptr(pos), _stream()))
     return off, pos
+
+
+KERNEL_BOX, KERNEL_TRIANGULAR, KERNEL_GAUSSIAN = 0, 1, 2
+
+
+def smoothing_kernel(kind: int, K: int):
+    """Weights of a smoothing kernel (s3_smoothing_kernel, computed by the library on the host) as a float32 GPU tensor."""
+    import torch
+    host = (C.c_float * K)()
+    _check(lib().s3_smoothing_kernel(kind, K, host))
+    return torch.tensor(list(host), dtype=torch.float32).cuda()
+
+
+def select_spans(scores, kernel, n_centers: int, nms_radius: int, rel_threshold: float, max_half_len: int,
+                 want_density: bool = False):
+    """s3_select_spans: scores [L] fp32, kernel [K] fp32 (GPU).  Returns (center, center_density, span_lo, span_hi,
+    n_found, density | None)."""
+    import torch
+    assert scores.is_cuda and scores.is_contiguous() and scores.dtype == torch.float32 and scores.dim() == 1
+    assert kernel.is_cuda and kernel.is_contiguous() and kernel.dtype == torch.float32 and kernel.dim() == 1
+    L, dev = scores.numel(), scores.device
+    ws = torch.empty(max(int(lib().s3_select_spans_workspace(L)), 1), dtype=torch.uint8, device=dev)
+    center = torch.empty(n_centers, dtype=torch.int32, device=dev)
+    dens_c = torch.empty(n_centers, dtype=torch.float32, device=dev)
+    lo = torch.empty(n_centers, dtype=torch.int32, device=dev)
+    hi = torch.empty(n_centers, dtype=torch.int32, device=dev)
+    found = torch.empty(1, dtype=torch.int32, device=dev)
+    D = torch.empty(L, dtype=torch.float32, device=dev) if want_density else None
+    _check(lib().s3_select_spans(_ptr(scores), L, _ptr(kernel), kernel.numel(), n_centers, nms_radius, rel_threshold,
+                                 max_half_len, _ptr(D), _ptr(center), _ptr(dens_c), _ptr(lo), _ptr(hi), _ptr(found),
+                                 _ptr(ws), ws.numel(), _stream()))
+    return center, dens_c, lo, hi, found, D
+
+
+def fuse_indices(n_positions: int, span_lo, span_hi, n_spans, extra=None, lead: int = 0, tail: int = 0):
+    """s3_fuse_indices: returns (mask uint8 [L], idx int32 [L], n_out int32 [1]); n_spans is a GPU int32 [1] or None."""
+    import torch
+    dev = span_lo.device
+    ws = torch.empty(max(int(lib().s3_fuse_indices_workspace(n_positions)), 1), dtype=torch.uint8, device=dev)
+    mask = torch.empty(n_positions, dtype=torch.uint8, device=dev)
+    idx = torch.empty(n_positions, dtype=torch.int32, device=dev)
+    n_out = torch.empty(1, dtype=torch.int32, device=dev)
+    assert span_lo.dtype == torch.int32 and span_hi.dtype == torch.int32 and span_lo.numel() == span_hi.numel()
+    if extra is not None:
+        assert extra.is_cuda and extra.dtype == torch.int32 and extra.is_contiguous()
+    _check(lib().s3_fuse_indices(n_positions, _ptr(span_lo), _ptr(span_hi), _ptr(n_spans), span_lo.numel(), _ptr(extra),
+                                 0 if extra is None else extra.numel(), lead, tail, _ptr(mask), _ptr(idx), _ptr(n_out),
+                                 _ptr(ws), ws.numel(), _stream()))
+    return mask, idx, n_out
