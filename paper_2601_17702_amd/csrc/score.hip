@@ -46,7 +46,6 @@ struct ScoreArgs {
     unsigned long long* part;        // [ngroup][L] partial sums of head groups (ngroup > 1)
     int pb, npb, heads_per, ngroup, sorted;   // position blocks / head groups of the gather
     long long* wfix;                 // [nW]
-    unsigned char* dead;             // [nW]
     long long* tmaxv;                // [ntile]
     int* tmaxi;                      // [ntile]
     int ntile;
@@ -134,7 +133,7 @@ __global__ __launch_bounds__(kPrepThreads) void sc_prep_kernel(ScoreArgs a) {
             if (sacc) {
                 const int freq = off[i + 1] - off[i];
                 if (freq > 0 && !(a.max_freq > 0 && freq > a.max_freq))
-                    w[j] = (double)sacc * inv / (log(1.0 + (double)freq) + 1.0);
+                    w[j] = (double)sacc * inv / ((double)logf(1.0f + (float)freq) + 1.0);
             }
         }
         c += w[j] > 0.0 ? 1 : 0;
@@ -163,13 +162,14 @@ __global__ __launch_bounds__(kPrepThreads) void sc_prep_kernel(ScoreArgs a) {
 // (64-bit fixed point, so the order of the additions does not matter), then stores the block: into S when there
 // is one head group, else into that group's partial array (summed by sc_reduce_kernel).  No global atomics.
 // A wavefront takes 64 lists at a time: lane l fetches weight and feature of list l and the part of the list that
-// lies in the block -- from the index's block table when there is one; else, for lists sorted by position, by a
-// search; else the whole list, every posting filtered -- then the lists are walked kWalk at a time (lanes over
-// postings) so that kWalk independent loads are in flight.
+// lies in the block (its segment) -- from the index's block table when there is one; else, for lists sorted by
+// position, by a search; else the whole list, every posting filtered.  Segments of more than 2 G postings are then
+// walked one at a time by the whole wavefront, the others G lanes per segment (64 / G segments per load
+// instruction); G is 16 or 32, picked on the host from the mean segment length.
 constexpr int kScatterThreads = 1024;
-constexpr int kWalk = 8;             // posting loads a wavefront keeps in flight
+constexpr int kLong = 8;             // loads in flight while a long segment is walked by the whole wavefront
+constexpr int kShortSlots = 8;       // loads in flight while short segments are walked by lane groups
 constexpr int kNarrowMin = 128;      // sorted lists longer than this are narrowed to the position block by search
-constexpr int kWalkRounds = 4;       // rounds in which kWalk lists advance together before the long rest is walked alone
 constexpr int kMaxPB = 1 << kS3PosBlockLog2;
 
 // First index in [b, e) whose position is >= key (e if none); pos[b .. e) ascending.  Eight-way search: the seven
@@ -196,11 +196,14 @@ __device__ __forceinline__ int lower_bound_pos(const int32_t* pos, int b, int e,
     return b + c;
 }
 
+template <int G>
 __global__ __launch_bounds__(kScatterThreads) void sc_scatter_lds_kernel(ScoreArgs a) {
     extern __shared__ unsigned long long sblk[];
     __shared__ unsigned long long wmx[kScatterThreads / 64];
+    __shared__ int4 recs_all[kScatterThreads];           // per wavefront: (begin, length, weight) of the batch's segments
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    int4* const recs = recs_all + wave * 64;
     const int blk = blockIdx.x;
     const int64_t p0 = (int64_t)blk * a.pb;
     const int64_t p1 = p0 + a.pb < a.L ? p0 + a.pb : a.L;
@@ -226,11 +229,15 @@ __global__ __launch_bounds__(kScatterThreads) void sc_scatter_lds_kernel(ScoreAr
         const int32_t* tab = a.btab ? a.btab + (size_t)h * a.n_feat * nbk : nullptr;
         const ActiveList* act = a.act + (size_t)h * a.n_feat + (size_t)r * kRange;
         const int n_act = a.nact[hr];
-        for (int i0 = wave * 64; i0 < n_act; i0 += (kScatterThreads / 64) * 64) {
+        constexpr int kStep = (kScatterThreads / 64) * 64;
+        uint4 raw_next = make_uint4(0, 0, 0, 0);
+        if (wave * 64 + lane < n_act) raw_next = *reinterpret_cast<const uint4*>(act + wave * 64 + lane);
+        for (int i0 = wave * 64; i0 < n_act; i0 += kStep) {
             unsigned long long wf = 0;
             int b = 0, e = 0;
+            const uint4 raw = raw_next;                      // weight and feature in one load, fetched one batch ahead
+            if (i0 + kStep + lane < n_act) raw_next = *reinterpret_cast<const uint4*>(act + i0 + kStep + lane);
             if (i0 + lane < n_act) {
-                const uint4 raw = *reinterpret_cast<const uint4*>(act + i0 + lane);      // weight and feature in one load
                 const double lw = __longlong_as_double((long long)(((unsigned long long)raw.y << 32) | raw.x));
                 wf = (unsigned long long)llrint(lw * scale);
                 if (wf) {
@@ -254,102 +261,73 @@ __global__ __launch_bounds__(kScatterThreads) void sc_scatter_lds_kernel(ScoreAr
                     }
                 }
             }
-            unsigned long long m = __ballot(e > b);
-            while (m) {
-                int bb[kWalk], ee[kWalk];
-                unsigned long long ww[kWalk];
+            // this batch's segments (the part of each list that lies in the block) go to the wavefront's records
+            const int n = wf ? max(e - b, 0) : 0;
+            recs[lane] = make_int4(b, n, (int)(unsigned)wf, (int)(unsigned)(wf >> 32));
+            // long segments: one at a time, the whole wavefront, kLong loads in flight
+            unsigned long long ml = __ballot(n > 2 * G);
+            while (ml) {
+                const int src = (int)__builtin_ctzll(ml);
+                ml &= ml - 1;
+                const int sb = __builtin_amdgcn_readlane(b, src), sn = __builtin_amdgcn_readlane(n, src);
+                const unsigned long long w = ((unsigned long long)(unsigned)__builtin_amdgcn_readlane((int)(unsigned)(wf >> 32), src) << 32) |
+                                             (unsigned)__builtin_amdgcn_readlane((int)(unsigned)wf, src);
+                const int32_t* lp = pos + sb;                              // uniform base, lanes add a 32-bit offset
+                for (int c0 = 0; c0 < sn; c0 += 64 * kLong) {
+                    int32_t pq[kLong];
 #pragma unroll
-                for (int j = 0; j < kWalk; ++j) {
-                    const int src = m ? (int)__builtin_ctzll(m) : -1;
-                    if (m) m &= m - 1;
-                    bb[j] = __builtin_amdgcn_readlane(b, src < 0 ? 0 : src);
-                    ee[j] = src < 0 ? bb[j] : __builtin_amdgcn_readlane(e, src);
-                    const unsigned lo = __builtin_amdgcn_readlane((unsigned)wf, src < 0 ? 0 : src);
-                    const unsigned hi = __builtin_amdgcn_readlane((unsigned)(wf >> 32), src < 0 ? 0 : src);
-                    ww[j] = ((unsigned long long)hi << 32) | lo;
-                }
-                // the kWalk lists side by side, 64 postings of each per round, for up to kWalkRounds rounds
-                int longest = 0;
-#pragma unroll
-                for (int j = 0; j < kWalk; ++j) longest = max(longest, ee[j] - bb[j]);
-                const int rounds = min((longest + 63) >> 6, kWalkRounds);
-                for (int rd = 0; rd < rounds; ++rd) {
-                    int32_t pp[kWalk];
-#pragma unroll
-                    for (int j = 0; j < kWalk; ++j) {
-                        const int q = bb[j] + rd * 64 + lane;
-                        pp[j] = q < ee[j] ? pos[q] : -1;
+                    for (int u = 0; u < kLong; ++u) {
+                        const int q = c0 + u * 64 + lane;
+                        pq[u] = q < sn ? lp[q] : -1;
                     }
 #pragma unroll
-                    for (int j = 0; j < kWalk; ++j) {
-                        const unsigned rr = (unsigned)((int64_t)pp[j] - p0);
-                        if (pp[j] >= 0 && rr < span) atomicAdd(&sblk[rr], ww[j]);
+                    for (int u = 0; u < kLong; ++u) {
+                        const unsigned rr = (unsigned)pq[u] - (unsigned)p0;
+                        if (pq[u] >= 0 && rr < span) atomicAdd(&sblk[rr], w);
                     }
                 }
+            }
+            // short segments (at most 2 G postings): G lanes per segment, 64 / G segments per load instruction,
+            // kShortSlots load instructions in flight
+            constexpr int LPS = 64 / G;
+            const int grp = lane / G, sub = lane % G;
+            unsigned long long ms = __ballot(n > 0 && n <= 2 * G);
+            while (ms) {
+                int4 rc[kShortSlots];
+                bool two = false;
 #pragma unroll
-                for (int j = 0; j < kWalk; ++j)     // rest of a very long list, kWalk loads in flight per step
-                    for (int q0 = bb[j] + 64 * kWalkRounds + lane; q0 - lane < ee[j]; q0 += 64 * kWalk) {
-                        int32_t pq[kWalk];
+                for (int u = 0; u < kShortSlots; ++u) {
+                    int idx = -1;
 #pragma unroll
-                        for (int u = 0; u < kWalk; ++u) pq[u] = q0 + u * 64 < ee[j] ? pos[q0 + u * 64] : -1;
-#pragma unroll
-                        for (int u = 0; u < kWalk; ++u) {
-                            const unsigned rr = (unsigned)((int64_t)pq[u] - p0);
-                            if (pq[u] >= 0 && rr < span) atomicAdd(&sblk[rr], ww[j]);
-                        }
+                    for (int g = 0; g < LPS; ++g) {                        // the next LPS segments, one per lane group
+                        const int sbit = ms ? (int)__builtin_ctzll(ms) : -1;
+                        if (ms) ms &= ms - 1;
+                        idx = grp == g ? sbit : idx;
                     }
+                    rc[u] = idx >= 0 ? recs[idx] : make_int4(0, 0, 0, 0);
+                    two = two || rc[u].y > G;
+                }
+                const int chunks = __any(two) ? 2 : 1;
+                for (int c = 0; c < chunks; ++c) {
+                    int32_t pq[kShortSlots];
+#pragma unroll
+                    for (int u = 0; u < kShortSlots; ++u) {
+                        const int q = c * G + sub;
+                        pq[u] = q < rc[u].y ? pos[rc[u].x + q] : -1;
+                    }
+#pragma unroll
+                    for (int u = 0; u < kShortSlots; ++u) {
+                        const unsigned rr = (unsigned)pq[u] - (unsigned)p0;
+                        const unsigned long long w = ((unsigned long long)(unsigned)rc[u].w << 32) | (unsigned)rc[u].z;
+                        if (pq[u] >= 0 && rr < span) atomicAdd(&sblk[rr], w);
+                    }
+                }
             }
         }
     }
     __syncthreads();
     unsigned long long* dst = a.ngroup > 1 ? a.part + (size_t)blockIdx.y * a.L : a.sfix;
     for (int64_t i = tid; i < (int64_t)span; i += kScatterThreads) dst[p0 + i] = sblk[i];
-}
-
-__global__ __launch_bounds__(256) void sc_reduce_kernel(ScoreArgs a) {
-    for (int64_t t = (int64_t)blockIdx.x * 256 + threadIdx.x; t < a.L; t += (int64_t)gridDim.x * 256) {
-        unsigned long long s = 0;
-        for (int g = 0; g < a.ngroup; ++g) s += a.part[(size_t)g * a.L + t];
-        a.sfix[t] = s;
-    }
-}
-
-// Span pooling (exact sliding sums in integers), the fp32 scores, and the best window of every tile of kTileW
-// windows (one wavefront per tile, kRun consecutive windows per lane; larger value wins, ties -> smaller start).
-__global__ __launch_bounds__(256) void sc_pool_kernel(ScoreArgs a) {
-    const double inv = ldexp(1.0, -exp_s(a.wmax[a.n_heads * a.nr], a.hb));
-    if (a.scores_out)
-        for (int64_t t = (int64_t)blockIdx.x * 256 + threadIdx.x; t < a.L; t += (int64_t)gridDim.x * 256)
-            a.scores_out[t] = (float)((double)a.sfix[t] * inv);
-    const int lane = threadIdx.x & 63;
-    const int64_t tile = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
-    if (tile >= a.ntile) return;
-    const int64_t s0 = tile * kTileW + (int64_t)lane * kRun;
-    long long bv = -1;
-    int bi = 0x7FFFFFFF;
-    if (s0 < a.nW) {
-        unsigned long long acc = 0;
-        for (int t = 0; t < a.len; ++t) acc += a.sfix[s0 + t];
-        a.wfix[s0] = (long long)acc;
-        a.dead[s0] = 0;
-        bv = (long long)acc;
-        bi = (int)s0;
-        for (int j = 1; j < kRun && s0 + j < a.nW; ++j) {
-            acc += a.sfix[s0 + j + a.len - 1] - a.sfix[s0 + j - 1];
-            a.wfix[s0 + j] = (long long)acc;
-            a.dead[s0 + j] = 0;
-            if ((long long)acc > bv) { bv = (long long)acc; bi = (int)(s0 + j); }
-        }
-    }
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) {
-        unsigned int lo = (unsigned int)__shfl_xor((int)(unsigned int)(unsigned long long)bv, o);
-        unsigned int hi = (unsigned int)__shfl_xor((int)(unsigned int)((unsigned long long)bv >> 32), o);
-        long long ov = (long long)(((unsigned long long)hi << 32) | lo);
-        int oi = __shfl_xor(bi, o);
-        if (ov > bv || (ov == bv && oi < bi)) { bv = ov; bi = oi; }
-    }
-    if (lane == 0) { a.tmaxv[tile] = bv; a.tmaxi[tile] = bi; }
 }
 
 // (value, index) argmax over the block: larger value wins, ties -> smaller index; value -1 = nothing
@@ -378,20 +356,157 @@ __device__ __forceinline__ void block_argmax(long long& v, int& i, long long* sv
     v = bv; i = bi;
 }
 
-// Greedy Top-B with optional suppression of overlapping windows: per round the best tile maximum, then the tiles
-// the suppression touched are searched again.  One small workgroup: the rounds depend on each other.
+// S = sum of the head groups' partial arrays.  64 positions per workgroup, four threads per position (each takes
+// every fourth group), so that a short context still fills the chip and every thread's loads are independent.
+__global__ __launch_bounds__(256) void sc_reduce_kernel(ScoreArgs a) {
+    __shared__ unsigned long long partial[4][64];
+    const int p = threadIdx.x & 63, q = threadIdx.x >> 6;
+    const int64_t t = (int64_t)blockIdx.x * 64 + p;
+    unsigned long long s0 = 0, s1 = 0;
+    if (t < a.L) {
+        int g = q;
+        for (; g + 4 < a.ngroup; g += 8) {
+            s0 += a.part[(size_t)g * a.L + t];
+            s1 += a.part[(size_t)(g + 4) * a.L + t];
+        }
+        if (g < a.ngroup) s0 += a.part[(size_t)g * a.L + t];
+    }
+    partial[q][p] = s0 + s1;
+    __syncthreads();
+    if (q == 0 && t < a.L) a.sfix[t] = partial[0][p] + partial[1][p] + partial[2][p] + partial[3][p];
+}
+
+// Inclusive prefix sum of one 64-bit value per thread over the block (wrap-around arithmetic: exact differences).
+template <int NT>
+__device__ __forceinline__ unsigned long long block_incl_scan_u64(unsigned long long v, unsigned long long* wsum) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+        const unsigned int lo = (unsigned int)__shfl_up((int)(unsigned int)v, o);
+        const unsigned int hi = (unsigned int)__shfl_up((int)(unsigned int)(v >> 32), o);
+        if (lane >= o) v += ((unsigned long long)hi << 32) | lo;
+    }
+    if (lane == 63) wsum[wave] = v;
+    __syncthreads();
+    unsigned long long base = 0;
+#pragma unroll
+    for (int w = 0; w < NT / 64; ++w) base += w < wave ? wsum[w] : 0ull;
+    __syncthreads();
+    return v + base;
+}
+
+// Span pooling, the fp32 scores, and the best window of every tile of kTileW windows (one workgroup per tile).
+// The tile's positions are staged in LDS and turned into prefix sums there, so a window costs two LDS reads
+// whatever its length: W[s] = P[s + len - 1] - P[s - 1], exact in 64-bit integers.  Larger value wins, ties ->
+// smaller start.
+constexpr int kPoolThreads = 256;
+constexpr int kPoolMaxLen = 4096;      // longer windows take sc_pool_wide_kernel
+
+__global__ __launch_bounds__(kPoolThreads) void sc_pool_kernel(ScoreArgs a) {
+    extern __shared__ unsigned long long pre[];          // [kTileW + len - 1 (+ padding)] prefix sums
+    __shared__ unsigned long long wsum[kPoolThreads / 64];
+    __shared__ long long sv[kPoolThreads / 64];
+    __shared__ int si[kPoolThreads / 64];
+    const int tid = threadIdx.x;
+    const double inv = ldexp(1.0, -exp_s(a.wmax[a.n_heads * a.nr], a.hb));
+    const int64_t s0 = (int64_t)blockIdx.x * kTileW;
+    const int64_t tend = (int)blockIdx.x == a.ntile - 1 ? a.L : s0 + kTileW;      // positions whose fp32 score this tile writes
+    const int n_in = (int)(min(a.L, s0 + kTileW + a.len - 1) - s0);               // positions the tile's windows read
+    constexpr int kPer = (kTileW + kPoolMaxLen + kPoolThreads - 1) / kPoolThreads;
+    const int per = (n_in + kPoolThreads - 1) / kPoolThreads;                     // consecutive positions per thread (<= kPer)
+    // each thread sums its own run, the block scans the run totals, the thread writes its run's prefixes
+    unsigned long long run = 0;
+    for (int j = 0; j < per; ++j) {
+        const int i = tid * per + j;
+        if (i < n_in) {
+            const unsigned long long v = a.sfix[s0 + i];
+            if (a.scores_out && s0 + i < tend) a.scores_out[s0 + i] = (float)((double)v * inv);
+            run += v;
+            pre[i] = run;
+        }
+    }
+    (void)kPer;
+    const unsigned long long incl = block_incl_scan_u64<kPoolThreads>(run, wsum);
+    const unsigned long long base = incl - run;
+    for (int j = 0; j < per; ++j) {
+        const int i = tid * per + j;
+        if (i < n_in) pre[i] += base;
+    }
+    __syncthreads();
+    long long bv = -1;
+    int bi = 0x7FFFFFFF;
+    for (int q = tid; q < kTileW; q += kPoolThreads) {                            // ascending starts per thread
+        const int64_t sw = s0 + q;
+        if (sw < a.nW) {
+            const long long w = (long long)(pre[q + a.len - 1] - (q ? pre[q - 1] : 0ull));
+            a.wfix[sw] = w;
+            if (w > bv) { bv = w; bi = (int)sw; }
+        }
+    }
+    block_argmax<kPoolThreads>(bv, bi, sv, si);
+    if (tid == 0) { a.tmaxv[blockIdx.x] = bv; a.tmaxi[blockIdx.x] = bi; }
+}
+
+// The same for windows longer than kPoolMaxLen: sliding sums from global memory, one wavefront per tile.
+__global__ __launch_bounds__(256) void sc_pool_wide_kernel(ScoreArgs a) {
+    const double inv = ldexp(1.0, -exp_s(a.wmax[a.n_heads * a.nr], a.hb));
+    if (a.scores_out)
+        for (int64_t t = (int64_t)blockIdx.x * 256 + threadIdx.x; t < a.L; t += (int64_t)gridDim.x * 256)
+            a.scores_out[t] = (float)((double)a.sfix[t] * inv);
+    const int lane = threadIdx.x & 63;
+    const int64_t tile = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (tile >= a.ntile) return;
+    const int64_t s0 = tile * kTileW + (int64_t)lane * kRun;
+    long long bv = -1;
+    int bi = 0x7FFFFFFF;
+    if (s0 < a.nW) {
+        unsigned long long acc = 0;
+        for (int t = 0; t < a.len; ++t) acc += a.sfix[s0 + t];
+        a.wfix[s0] = (long long)acc;
+        bv = (long long)acc;
+        bi = (int)s0;
+        for (int j = 1; j < kRun && s0 + j < a.nW; ++j) {
+            acc += a.sfix[s0 + j + a.len - 1] - a.sfix[s0 + j - 1];
+            a.wfix[s0 + j] = (long long)acc;
+            if ((long long)acc > bv) { bv = (long long)acc; bi = (int)(s0 + j); }
+        }
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+        unsigned int lo = (unsigned int)__shfl_xor((int)(unsigned int)(unsigned long long)bv, o);
+        unsigned int hi = (unsigned int)__shfl_xor((int)(unsigned int)((unsigned long long)bv >> 32), o);
+        long long ov = (long long)(((unsigned long long)hi << 32) | lo);
+        int oi = __shfl_xor(bi, o);
+        if (ov > bv || (ov == bv && oi < bi)) { bv = ov; bi = oi; }
+    }
+    if (lane == 0) { a.tmaxv[tile] = bv; a.tmaxi[tile] = bi; }
+}
+
+// Greedy Top-B with optional suppression of overlapping windows.  One small workgroup: the rounds depend on each
+// other.  The tile maxima live in LDS (up to kTopCache tiles; in global memory beyond that); a round takes the best
+// one, then searches the tiles again that the new span's suppression touches.  Whether a window is still alive
+// follows from the spans chosen so far (kept in LDS): no flag array in memory, one global round trip per round.
+constexpr int kTopCache = 4096;
+
 __global__ __launch_bounds__(kTopThreads) void sc_topb_kernel(ScoreArgs a) {
     __shared__ long long sv[kTopThreads / 64];
     __shared__ int si[kTopThreads / 64];
+    __shared__ long long cv[kTopCache];
+    __shared__ int ci[kTopCache];
+    __shared__ int sel[1024];
     const int tid = threadIdx.x;
+    const bool cached = a.ntile <= kTopCache;
     const double inv = ldexp(1.0, -exp_s(a.wmax[a.n_heads * a.nr], a.hb));
+    if (cached)
+        for (int t = tid; t < a.ntile; t += kTopThreads) { cv[t] = a.tmaxv[t]; ci[t] = a.tmaxi[t]; }
+    __syncthreads();
     int found = 0;
     for (int r = 0; r < a.top_b; ++r) {
         long long v = -1;
         int i = 0x7FFFFFFF;
         for (int t = tid; t < a.ntile; t += kTopThreads) {
-            long long tv = a.tmaxv[t];
-            int ti = a.tmaxi[t];
+            const long long tv = cached ? cv[t] : a.tmaxv[t];
+            const int ti = cached ? ci[t] : a.tmaxi[t];
             if (tv > v || (tv == v && ti < i)) { v = tv; i = ti; }
         }
         block_argmax<kTopThreads>(v, i, sv, si);
@@ -399,24 +514,39 @@ __global__ __launch_bounds__(kTopThreads) void sc_topb_kernel(ScoreArgs a) {
         if (tid == 0) {
             a.span_start[r] = i;
             a.span_score[r] = (float)((double)v * inv);
+            sel[r] = i;
         }
         found = r + 1;
-        const int64_t lo = a.nms ? max((int64_t)0, (int64_t)i - a.len + 1) : i;
-        const int64_t hi = a.nms ? min(a.nW - 1, (int64_t)i + a.len - 1) : i;
-        for (int64_t s = lo + tid; s <= hi; s += kTopThreads) a.dead[s] = 1;
         __syncthreads();
+        const int reach = a.nms ? a.len - 1 : 0;              // windows within `reach` of a chosen start are gone
+        const int64_t lo = max((int64_t)0, (int64_t)i - reach), hi = min(a.nW - 1, (int64_t)i + reach);
         for (int t = (int)(lo / kTileW); t <= (int)(hi / kTileW); ++t) {
-            long long tv = -1;
-            int ti = 0x7FFFFFFF;
-            for (int q = tid; q < kTileW; q += kTopThreads) {      // ascending starts per thread: the first best one is kept
-                const int64_t s = (int64_t)t * kTileW + q;
-                if (s < a.nW && !a.dead[s]) {
-                    const long long wv = a.wfix[s];
-                    if (wv > tv) { tv = wv; ti = (int)s; }
+            const int64_t t0 = (int64_t)t * kTileW;
+            long long w[kTileW / kTopThreads];
+#pragma unroll
+            for (int q = 0; q < kTileW / kTopThreads; ++q) {  // all loads first: one round trip
+                const int64_t sw = t0 + q * kTopThreads + tid;
+                w[q] = sw < a.nW ? a.wfix[sw] : -1;
+            }
+            for (int j = 0; j < found; ++j) {                 // chosen spans that reach into this tile
+                const int64_t c = sel[j];
+                if (c + reach < t0 || c - reach >= t0 + kTileW) continue;
+#pragma unroll
+                for (int q = 0; q < kTileW / kTopThreads; ++q) {
+                    const int64_t sw = t0 + q * kTopThreads + tid;
+                    if (sw >= c - reach && sw <= c + reach) w[q] = -1;
                 }
             }
+            long long tv = -1;
+            int ti = 0x7FFFFFFF;
+#pragma unroll
+            for (int q = 0; q < kTileW / kTopThreads; ++q)    // ascending starts per thread: the first best one is kept
+                if (w[q] > tv) { tv = w[q]; ti = (int)(t0 + q * kTopThreads + tid); }
             block_argmax<kTopThreads>(tv, ti, sv, si);
-            if (tid == 0) { a.tmaxv[t] = tv; a.tmaxi[t] = ti; }
+            if (tid == 0) {
+                if (cached) { cv[t] = tv; ci[t] = ti; }
+                else { a.tmaxv[t] = tv; a.tmaxi[t] = ti; }
+            }
         }
         __syncthreads();
     }
@@ -425,7 +555,7 @@ __global__ __launch_bounds__(kTopThreads) void sc_topb_kernel(ScoreArgs a) {
 }
 
 struct Layout {
-    size_t wmax, nact, sfix, wfix, dead, tmaxv, tmaxi, part, act, total;
+    size_t wmax, nact, sfix, wfix, tmaxv, tmaxi, part, act, total;
     int nr, pb, npb, heads_per, ngroup;   // feature ranges per head; position blocks and head groups of the gather
 };
 
@@ -440,7 +570,6 @@ Layout layout(int n_heads, int n_feat, int64_t L) {
     l.nact = take((size_t)n_heads * l.nr * 4);
     l.sfix = take((size_t)L * 8);
     l.wfix = take((size_t)L * 8);
-    l.dead = take((size_t)L);
     l.tmaxv = take(ntile * 8);
     l.tmaxi = take(ntile * 4);
     // position blocks of at most kMaxPB scores (128 KB of LDS); enough head groups for about one workgroup per compute unit
@@ -507,7 +636,6 @@ extern "C" int s3_coactivate_score(const s3_index* idx, const int32_t* qids, con
     a.sfix = (unsigned long long*)(base + l.sfix);
     a.act = (ActiveList*)(base + l.act);
     a.wfix = (long long*)(base + l.wfix);
-    a.dead = (unsigned char*)(base + l.dead);
     a.tmaxv = (long long*)(base + l.tmaxv);
     a.tmaxi = (int*)(base + l.tmaxi);
     a.part = (unsigned long long*)(base + l.part);
@@ -516,17 +644,25 @@ extern "C" int s3_coactivate_score(const s3_index* idx, const int32_t* qids, con
     a.scores_out = scores_out; a.span_start = span_start; a.span_score = span_score; a.n_found = n_found;
 
     hipStream_t st = (hipStream_t)stream;
-    static S3LdsOnce once_prep, once_scatter;
+    static S3LdsOnce once_prep, once_scatter[2];
     const int prep_lds = (a.n_feat < kRange ? a.n_feat : kRange) * 8;
     if (int rc = s3_allow_lds(once_prep, (const void*)sc_prep_kernel, kRange * 8)) return rc;
-    if (int rc = s3_allow_lds(once_scatter, (const void*)sc_scatter_lds_kernel, kMaxPB * 8)) return rc;
+    // lanes per short segment: from the mean length of a list's part in one position block
+    const double mean_seg = (double)v.tokens * a.k / ((double)a.n_feat * l.npb);
+    const bool narrow = mean_seg <= 20.0;
+    auto scatter = narrow ? sc_scatter_lds_kernel<16> : sc_scatter_lds_kernel<32>;
+    if (int rc = s3_allow_lds(once_scatter[narrow], (const void*)scatter, kMaxPB * 8)) return rc;
     // five launches: query weights, gather, sum of the head groups, pooling + tile maxima, Top-B
     hipLaunchKernelGGL(sc_prep_kernel, dim3((unsigned)a.nr, (unsigned)a.n_heads), dim3(kPrepThreads), (size_t)prep_lds, st, a);
-    hipLaunchKernelGGL(sc_scatter_lds_kernel, dim3((unsigned)a.npb, (unsigned)a.ngroup), dim3(kScatterThreads),
-                       (size_t)a.pb * 8, st, a);
-    auto blocks = [](size_t n, size_t per) { size_t b = (n + per - 1) / per; return (unsigned)(b < 1 ? 1 : (b > 65536 ? 65536 : b)); };
-    if (a.ngroup > 1) hipLaunchKernelGGL(sc_reduce_kernel, dim3(blocks((size_t)a.L, 256)), dim3(256), 0, st, a);
-    hipLaunchKernelGGL(sc_pool_kernel, dim3((unsigned)((a.ntile + 3) / 4)), dim3(256), 0, st, a);
+    hipLaunchKernelGGL(scatter, dim3((unsigned)a.npb, (unsigned)a.ngroup), dim3(kScatterThreads), (size_t)a.pb * 8, st, a);
+    if (a.ngroup > 1) hipLaunchKernelGGL(sc_reduce_kernel, dim3((unsigned)((a.L + 63) / 64)), dim3(256), 0, st, a);
+    if (a.len <= kPoolMaxLen) {
+        static S3LdsOnce once_pool;
+        if (int rc = s3_allow_lds(once_pool, (const void*)sc_pool_kernel, (kTileW + kPoolMaxLen) * 8)) return rc;
+        hipLaunchKernelGGL(sc_pool_kernel, dim3((unsigned)a.ntile), dim3(kPoolThreads), (size_t)(kTileW + a.len) * 8, st, a);
+    } else {
+        hipLaunchKernelGGL(sc_pool_wide_kernel, dim3((unsigned)((a.ntile + 3) / 4)), dim3(256), 0, st, a);
+    }
     hipLaunchKernelGGL(sc_topb_kernel, dim3(1), dim3(kTopThreads), 0, st, a);
     S3_HIP(hipGetLastError());
     return S3_OK;
