@@ -298,6 +298,52 @@ int64_t orc_fuse(int64_t L, const int32_t* lo, const int32_t* hi, int n_spans, c
     return n;
 }
 
+// ---- compact postings (Sec. 3.4 "CPU Index Size": contiguous integer arrays with delta encoding and optional
+// stop-feature pruning) ----
+// The form taken here: positions are cut into blocks of 2^block_log2; a posting is stored as its 16-bit offset
+// from the start of its block (the delta against the block base), and the postings are ordered block by block, inside a
+// block list by list (ascending feature id), inside a list in list order.  cstart [nblk * n_feat + 1] gives where the
+// segment of (block b, feature f) starts (entry b * n_feat + f; the next entry is its end); cfreq [n_feat] is the
+// length of each list that was kept.  A list longer than prune_freq is dropped whole when prune_freq > 0 (stop
+// feature).  Lists must ascend in position and lie below nblk << block_log2.  Returns the number of postings
+// kept, or -1 if a list does not ascend / leaves the range.
+int64_t orc_compact_encode(const int32_t* offsets, const int32_t* positions, int n_feat, int nblk, int block_log2,
+                           int32_t prune_freq, int32_t* cstart, uint16_t* delta, int32_t* cfreq) {
+    if (block_log2 < 1 || block_log2 > 16 || nblk < 1) return -1;
+    int64_t o = 0;
+    for (int f = 0; f < n_feat; ++f) {
+        const int32_t len = offsets[f + 1] - offsets[f];
+        cfreq[f] = (prune_freq > 0 && len > prune_freq) ? 0 : len;
+        for (int32_t i = offsets[f]; i < offsets[f + 1]; ++i) {
+            if (positions[i] < 0 || (positions[i] >> block_log2) >= nblk) return -1;
+            if (i > offsets[f] && positions[i] <= positions[i - 1]) return -1;
+        }
+    }
+    for (int b = 0; b < nblk; ++b)
+        for (int f = 0; f < n_feat; ++f) {
+            cstart[(size_t)b * n_feat + f] = (int32_t)o;
+            if (cfreq[f] == 0) continue;
+            for (int32_t i = offsets[f]; i < offsets[f + 1]; ++i)
+                if ((positions[i] >> block_log2) == b) delta[o++] = (uint16_t)(positions[i] - (b << block_log2));
+        }
+    cstart[(size_t)nblk * n_feat] = (int32_t)o;
+    return o;
+}
+
+// The inverse: plain CSR (offsets [n_feat + 1], positions) of the lists that were kept.
+int64_t orc_compact_decode(const int32_t* cstart, const uint16_t* delta, int n_feat, int nblk, int block_log2,
+                           int32_t* offsets, int32_t* positions) {
+    int64_t o = 0;
+    for (int f = 0; f < n_feat; ++f) {
+        offsets[f] = (int32_t)o;
+        for (int b = 0; b < nblk; ++b)
+            for (int32_t i = cstart[(size_t)b * n_feat + f]; i < cstart[(size_t)b * n_feat + f + 1]; ++i)
+                positions[o++] = (b << block_log2) + (int32_t)delta[i];
+    }
+    offsets[n_feat] = (int32_t)o;
+    return o;
+}
+
 // Number of host threads orc_encode_topk uses (rows are independent; nothing else is threaded).
 int orc_threads(void) {
 #ifdef _OPENMP

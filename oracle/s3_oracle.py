@@ -50,6 +50,10 @@ def lib():
         L.orc_pool.restype = i64
         L.orc_topb.argtypes = [vp, i64, C.c_int, C.c_int, C.c_int, vp, vp]
         L.orc_threads.restype = C.c_int
+        L.orc_compact_encode.argtypes = [vp, vp, C.c_int, C.c_int, C.c_int, i32, vp, vp, vp]
+        L.orc_compact_encode.restype = i64
+        L.orc_compact_decode.argtypes = [vp, vp, C.c_int, C.c_int, C.c_int, vp, vp]
+        L.orc_compact_decode.restype = i64
         L.orc_smoothing_kernel.argtypes = [C.c_int, C.c_int, vp]
         L.orc_conv1d.argtypes = [vp, i64, vp, C.c_int, vp]
         L.orc_nms_peaks.argtypes = [vp, i64, C.c_int, C.c_int, vp, vp]
@@ -167,6 +171,30 @@ def topb(W, span_len, top_b, nms=True):
     scores = np.empty(top_b, np.float64)
     n = lib().orc_topb(_p(W), W.shape[0], int(span_len), int(top_b), int(bool(nms)), _p(starts), _p(scores))
     return starts[:n].copy(), scores[:n].copy()
+
+
+def compact_encode(offsets, positions, nblk, block_log2=14, prune_freq=0):
+    """Plain CSR -> (cstart [nblk * n_feat + 1], delta uint16 [kept], cfreq [n_feat])."""
+    offsets = np.ascontiguousarray(offsets, dtype=np.int32)
+    positions = np.ascontiguousarray(positions, dtype=np.int32)
+    n_feat = offsets.shape[0] - 1
+    cstart = np.empty(nblk * n_feat + 1, np.int32)
+    delta = np.empty(max(positions.shape[0], 1), np.uint16)
+    cfreq = np.empty(n_feat, np.int32)
+    n = lib().orc_compact_encode(_p(offsets), _p(positions), n_feat, int(nblk), int(block_log2), int(prune_freq),
+                                 _p(cstart), _p(delta), _p(cfreq))
+    if n < 0:
+        raise ValueError("orc_compact_encode: a list does not ascend or leaves the block range")
+    return cstart, delta[:n].copy(), cfreq
+
+
+def compact_decode(cstart, delta, n_feat, nblk, block_log2=14):
+    cstart = np.ascontiguousarray(cstart, dtype=np.int32)
+    delta = np.ascontiguousarray(delta, dtype=np.uint16)
+    offsets = np.empty(n_feat + 1, np.int32)
+    positions = np.empty(max(delta.shape[0], 1), np.int32)
+    n = lib().orc_compact_decode(_p(cstart), _p(delta), n_feat, int(nblk), int(block_log2), _p(offsets), _p(positions))
+    return offsets, positions[:n].copy()
 
 
 KERNEL_KINDS = {"box": 0, "triangular": 1, "gaussian": 2}

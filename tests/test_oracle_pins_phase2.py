@@ -99,3 +99,51 @@ def test_fuse_is_a_set_union():
         assert idx.tolist() == sorted(want) and np.array_equal(np.flatnonzero(mask), idx) and set(np.unique(mask)) <= {0, 1}
     mask, idx = orc.fuse(10, np.zeros(0, np.int32), np.zeros(0, np.int32), np.zeros(0, np.int32), 2, 3)
     assert idx.tolist() == [0, 1, 7, 8, 9]
+
+
+# ------------------------------------------------------------------ compact postings (Sec. 3.4 "CPU Index Size")
+def _random_csr(rng, n_feat, L, density):
+    lists = [np.flatnonzero(rng.random(L) < density * rng.random()).astype(np.int32) for _ in range(n_feat)]
+    lists[3] = np.arange(L, dtype=np.int32)                        # a stop feature: in every token
+    lists[5] = np.zeros(0, np.int32)                               # an empty list
+    offsets = np.concatenate([[0], np.cumsum([len(l) for l in lists])]).astype(np.int32)
+    return lists, offsets, np.concatenate(lists).astype(np.int32)
+
+
+def test_compact_postings_hand_case():
+    # block size 4 (block_log2 = 2), 2 blocks, 3 features: lists [1, 2, 5], [], [0, 4, 6, 7]
+    offsets = np.array([0, 3, 3, 7], np.int32)
+    positions = np.array([1, 2, 5, 0, 4, 6, 7], np.int32)
+    cstart, delta, cfreq = orc.compact_encode(offsets, positions, 2, block_log2=2)
+    # block 0: f0 -> 1, 2; f1 -> none; f2 -> 0.  block 1: f0 -> 5 - 4; f2 -> 4 - 4, 6 - 4, 7 - 4
+    assert cstart.tolist() == [0, 2, 2, 3, 4, 4, 7] and delta.tolist() == [1, 2, 0, 1, 0, 2, 3] and cfreq.tolist() == [3, 0, 4]
+    off2, pos2 = orc.compact_decode(cstart, delta, 3, 2, block_log2=2)
+    assert np.array_equal(off2, offsets) and np.array_equal(pos2, positions)
+    cstart, delta, cfreq = orc.compact_encode(offsets, positions, 2, block_log2=2, prune_freq=3)    # strict >: the list of 4 goes
+    assert cstart.tolist() == [0, 2, 2, 2, 3, 3, 3] and delta.tolist() == [1, 2, 1] and cfreq.tolist() == [3, 0, 0]
+    with pytest.raises(ValueError):
+        orc.compact_encode(offsets, np.array([2, 1, 5, 0, 4, 6, 7], np.int32), 2, block_log2=2)     # not ascending
+    with pytest.raises(ValueError):
+        orc.compact_encode(offsets, positions, 1, block_log2=2)                                      # beyond the blocks
+
+
+def test_compact_postings_round_trip_brute_force():
+    rng = np.random.default_rng(17)
+    n_feat, L, blk = 40, 1000, 7                                   # blocks of 128 positions, 8 blocks
+    lists, offsets, positions = _random_csr(rng, n_feat, L, 0.2)
+    nblk = (L + (1 << blk) - 1) >> blk
+    for prune in (0, 150):
+        cstart, delta, cfreq = orc.compact_encode(offsets, positions, nblk, block_log2=blk, prune_freq=prune)
+        kept = [l if not (prune > 0 and len(l) > prune) else l[:0] for l in lists]
+        assert cfreq.tolist() == [len(l) for l in kept] and len(delta) == sum(len(l) for l in kept)    # 2 bytes per kept posting
+        assert delta.max() < (1 << blk) and np.all(np.diff(cstart) >= 0) and cstart[0] == 0 and cstart[-1] == len(delta)
+        # every segment, from the definition: postings of list f that lie in block b, as offsets from the block's start
+        for b in range(nblk):
+            for f in range(n_feat):
+                seg = delta[cstart[b * n_feat + f]: cstart[b * n_feat + f + 1]]
+                want = kept[f][(kept[f] >> blk) == b] - (b << blk)
+                assert np.array_equal(seg, want)
+        off2, pos2 = orc.compact_decode(cstart, delta, n_feat, nblk, block_log2=blk)
+        assert np.array_equal(off2, np.concatenate([[0], np.cumsum([len(l) for l in kept])]))
+        assert np.array_equal(pos2, np.concatenate(kept))
+    assert prune and lists[3].shape[0] > prune                     # the stop feature was really dropped
