@@ -185,6 +185,43 @@ int s3_coactivate_score(const s3_index* idx, const int32_t* qids, const float* q
                         int32_t* n_found, void* ws, size_t ws_bytes, void* stream);
 
 /* ------------------------------------------------------------------------------------------
+ * Sec. 3.4 "CPU Index Size": the compact form of a finalized index -- contiguous integer arrays
+ * with delta encoding and optional stop-feature pruning -- and Sec. 3.5 scoring straight from it.
+ * Positions are cut into blocks of 16384; a posting is stored as its 16-bit offset from the start
+ * of its block, and the postings are ordered block by block, inside a block list by list
+ * (ascending feature id), inside a list in list order:
+ *     cstart [n_blocks * n_feat + 1] int32: entry b * n_feat + f is where the segment of (block b,
+ *            feature f) starts in delta; the next entry is its end
+ *     delta  [kept postings] uint16;  cfreq [n_feat] int32: length of each list (0: dropped)
+ * A list with more than prune_freq postings is dropped whole when prune_freq > 0 (a stop feature;
+ * scoring the compact index then equals scoring the plain one with max_freq = prune_freq).
+ * 2 bytes per posting instead of 4, and everything a scoring workgroup reads for its block of
+ * positions is one contiguous run of memory.
+ *
+ * s3_index_compact builds it on `stream` into `buf` (device, caller-owned, 256-byte aligned, at
+ * least s3_index_compact_bytes(idx) bytes -- sized for no pruning); *out is a small host handle
+ * (free with s3_cindex_destroy; the arrays live in buf and stay valid as long as buf does, also
+ * after the plain index is destroyed).  Needs an index fed implicit, increasing positions that lie
+ * below 64 * 16384 (S3_ESTATE otherwise, and before finalize).
+ * s3_cindex_export copies one head's arrays (any may be NULL): cstart_out [n_blocks * n_feat + 1],
+ * delta_out [max_postings] (only the first cstart[last] entries are meaningful), cfreq_out [n_feat];
+ * s3_cindex_info gives n_blocks and max_postings (= tokens * k).
+ * s3_coactivate_score_compact: as s3_coactivate_score, reading the compact index. */
+typedef struct s3_cindex s3_cindex;
+size_t s3_index_compact_bytes(const s3_index* idx);
+int s3_index_compact(const s3_index* idx, int32_t prune_freq, void* buf, size_t buf_bytes, s3_cindex** out,
+                     void* stream);
+void s3_cindex_destroy(s3_cindex* cidx);
+int s3_cindex_info(const s3_cindex* cidx, int* n_blocks, int64_t* max_postings);
+int s3_cindex_export(const s3_cindex* cidx, int head, int32_t* cstart_out, uint16_t* delta_out,
+                     int32_t* cfreq_out, void* stream);
+size_t s3_coactivate_score_compact_workspace(const s3_cindex* cidx, int64_t n_positions);
+int s3_coactivate_score_compact(const s3_cindex* cidx, const int32_t* qids, const float* qvals, int nq,
+                                int64_t n_positions, int span_len, int top_b, int32_t max_freq, int nms,
+                                float* scores_out, int32_t* span_start, float* span_score,
+                                int32_t* n_found, void* ws, size_t ws_bytes, void* stream);
+
+/* ------------------------------------------------------------------------------------------
  * Sec. 3.5 "Adaptive Granularity" and Alg. 1 Phase 2 (S' <- Conv1D(S); Idx <- NMS_Select(S', N)) with
  * a smoothing kernel of the caller's choice and variable-length spans.  The paper fixes the sizes
  * (App. B.3: kernel 48, 8 for QA; N = 40 centres) and leaves the weights, the suppression rule and

@@ -67,6 +67,20 @@ def lib():
         L.s3_fuse_indices_workspace.restype = sz
         L.s3_fuse_indices.argtypes = [i64, vp, vp, vp, ci, vp, i64, ci, ci, vp, vp, vp, vp, sz, vp]
         L.s3_fuse_indices.restype = ci
+        L.s3_index_compact_bytes.argtypes = [vp]
+        L.s3_index_compact_bytes.restype = sz
+        L.s3_index_compact.argtypes = [vp, i32, vp, sz, C.POINTER(vp), vp]
+        L.s3_index_compact.restype = ci
+        L.s3_cindex_destroy.argtypes = [vp]
+        L.s3_cindex_destroy.restype = None
+        L.s3_cindex_info.argtypes = [vp, C.POINTER(ci), C.POINTER(i64)]
+        L.s3_cindex_info.restype = ci
+        L.s3_cindex_export.argtypes = [vp, ci, vp, vp, vp, vp]
+        L.s3_cindex_export.restype = ci
+        L.s3_coactivate_score_compact_workspace.argtypes = [vp, i64]
+        L.s3_coactivate_score_compact_workspace.restype = sz
+        L.s3_coactivate_score_compact.argtypes = [vp, vp, vp, ci, i64, ci, ci, i32, ci, vp, vp, vp, vp, vp, sz, vp]
+        L.s3_coactivate_score_compact.restype = ci
         for name in ("s3_sae_encode_topk", "s3_sae_encode_topk_stream", "s3_index_create", "s3_index_append", "s3_index_finalize",
                      "s3_index_csr", "s3_index_build", "s3_coactivate_score"):
             getattr(L, name).restype = ci
@@ -223,9 +237,73 @@ class Index:
                                          _ptr(found), _ptr(ws), ws.numel(), _stream()))
         return starts, scores, found, S
 
+    def compact(self, prune_freq: int = 0):
+        """s3_index_compact: the compact form of this (finalized) index in a buffer of its own."""
+        return CompactIndex(self, prune_freq)
+
     def destroy(self):
         if getattr(self, "_h", None) and lib is not None:    # module globals are gone at interpreter shutdown
             lib().s3_index_destroy(self._h)
+            self._h = None
+
+    def __del__(self):
+        self.destroy()
+
+
+class CompactIndex:
+    """Compact form of a finalized Index (s3_index_compact): 16-bit block-relative postings in block-major order, a
+    segment table, optional stop-feature pruning.  Owns its buffer; independent of the Index it was built from."""
+
+    def __init__(self, index: "Index", prune_freq: int = 0):
+        import torch
+        need = int(lib().s3_index_compact_bytes(index._h))
+        self.buf = torch.empty(max(need, 256), dtype=torch.uint8, device="cuda")
+        h = C.c_void_p()
+        _check(lib().s3_index_compact(index._h, prune_freq, _ptr(self.buf), self.buf.numel(), C.byref(h), _stream()))
+        self._h = h
+        self.n_heads, self.n_feat, self.k = index.n_heads, index.n_feat, index.k
+        nb, mp = C.c_int(), C.c_int64()
+        _check(lib().s3_cindex_info(self._h, C.byref(nb), C.byref(mp)))
+        self.n_blocks, self.max_postings = nb.value, mp.value
+        self.nbytes = need
+
+    def arrays(self, head: int):
+        """Copies of one head's (cstart int32 [n_blocks * n_feat + 1], delta int16-view-of-uint16 [kept], cfreq [n_feat])."""
+        import torch
+        cs = torch.empty(self.n_blocks * self.n_feat + 1, dtype=torch.int32, device="cuda")
+        de = torch.empty(max(self.max_postings, 1), dtype=torch.int16, device="cuda")
+        cf = torch.empty(self.n_feat, dtype=torch.int32, device="cuda")
+        _check(lib().s3_cindex_export(self._h, head, _ptr(cs), _ptr(de), _ptr(cf), _stream()))
+        torch.cuda.synchronize()
+        return cs, de[: int(cs[-1].item())], cf
+
+    def score_workspace(self, n_positions: int) -> int:
+        return int(lib().s3_coactivate_score_compact_workspace(self._h, n_positions))
+
+    def coactivate_score(self, qids, qvals, n_positions: int, span_len: int, top_b: int, max_freq: int = 0,
+                         nms: bool = True, want_scores: bool = False, ws=None):
+        """As Index.coactivate_score, reading the compact index."""
+        import torch
+        assert qids.is_cuda and qids.is_contiguous() and qvals.is_contiguous()
+        assert qids.dtype == torch.int32 and qvals.dtype == torch.float32 and qids.dim() == 3
+        assert qids.shape[0] == self.n_heads and qids.shape[2] == self.k and qvals.shape == qids.shape
+        dev = qids.device
+        need = self.score_workspace(n_positions)
+        if ws is None:
+            ws = torch.empty(need, dtype=torch.uint8, device=dev)
+        assert ws.numel() >= need
+        starts = torch.empty(top_b, dtype=torch.int32, device=dev)
+        scores = torch.empty(top_b, dtype=torch.float32, device=dev)
+        found = torch.empty(1, dtype=torch.int32, device=dev)
+        S = torch.empty(n_positions, dtype=torch.float32, device=dev) if want_scores else None
+        _check(lib().s3_coactivate_score_compact(self._h, _ptr(qids), _ptr(qvals), qids.shape[1], n_positions, span_len,
+                                                 top_b, max_freq, int(bool(nms)), _ptr(S), _ptr(starts), _ptr(scores),
+                                                 _ptr(found), _ptr(ws), ws.numel(), _stream()))
+        return starts, scores, found, S
+
+    def destroy(self):
+        if getattr(self, "_h", None) and lib is not None:
+            lib().s3_cindex_destroy(self._h)
             self._h = None
 
     def __del__(self):

@@ -479,7 +479,7 @@ void s3_index_view(const s3_index* idx, S3IndexView* v) {
     v->n_heads = idx->n_heads; v->n_feat = idx->n_feat; v->k = idx->k; v->tokens = idx->tokens;
     v->offsets = idx->d.offsets; v->off_stride = idx->d.off_stride;
     v->positions = idx->d.positions; v->pos_stride = idx->d.pos_stride;
-    v->finalized = idx->finalized; v->sorted = idx->sorted;
+    v->finalized = idx->finalized; v->sorted = idx->sorted; v->max_pos = idx->max_pos;
     v->btab = idx->btab; v->nblk = idx->nblk;
     v->btab_valid = idx->btab && idx->sorted && idx->max_pos < ((int64_t)idx->nblk << kS3PosBlockLog2);
 }

@@ -49,6 +49,7 @@ struct S3IndexView {
     int64_t off_stride, pos_stride;
     bool finalized;
     bool sorted;                 // every list ascends in position (implicit, increasing positions only)
+    int64_t max_pos;             // largest position appended (meaningful while sorted)
     // block table: btab[(h * n_feat + f) * (nblk - 1) + j - 1] = index, in head h's positions array, of the first
     // posting of list f whose position is >= j << kS3PosBlockLog2, j = 1 .. nblk - 1.  Null when there is none;
     // valid only for sorted lists whose positions are all below nblk << kS3PosBlockLog2 (btab_valid).
@@ -57,6 +58,17 @@ struct S3IndexView {
     bool btab_valid;
 };
 void s3_index_view(const s3_index* idx, S3IndexView* out);
+
+// Read-only view of a compact index for the scoring translation unit (defined in compact.hip).
+struct S3CompactView {
+    int n_heads, n_feat, k, nblk;
+    int64_t tokens;
+    const int32_t* cstart;       // [n_heads] x cstart_stride (nblk * n_feat + 1 entries used)
+    const uint16_t* delta;       // [n_heads] x delta_stride
+    const int32_t* cfreq;        // [n_heads][n_feat]
+    int64_t cstart_stride, delta_stride;
+};
+void s3_cindex_view(const s3_cindex* cidx, S3CompactView* out);
 
 // ---- prefix sums shared by the index and the scoring kernels ----
 // Inclusive prefix sums over the lanes of a wavefront / over each row of 16 lanes, by data-parallel-primitive

@@ -17,6 +17,8 @@
 
 #include <math.h>
 
+#include <type_traits>
+
 namespace {
 
 // A posting list with a non-zero query weight.
@@ -34,6 +36,11 @@ struct ScoreArgs {
     int64_t off_stride, pos_stride;
     const int32_t* btab;             // block table of the index (null: none or not usable)
     int nblk;                        // blocks the table covers
+    // compact index (all null / 0 for the plain one): 16-bit block-relative postings in block-major order
+    const uint16_t* delta;           // [n_heads] x delta_stride
+    const int32_t* cstart;           // [n_heads] x cstart_stride: start of segment (block b, feature f) at b * n_feat + f
+    const int32_t* cfreq;            // [n_heads][n_feat] list lengths (0: dropped)
+    int64_t delta_stride, cstart_stride;
     int n_heads, n_feat, k, nq;
     int nr;                          // feature ranges per head (sc_prep_kernel)
     int64_t L, nW;
@@ -120,7 +127,7 @@ __global__ __launch_bounds__(kPrepThreads) void sc_prep_kernel(ScoreArgs a) {
     }
     __syncthreads();
     constexpr int kPer = kRange / kPrepThreads;
-    const int32_t* off = a.offsets + (size_t)h * a.off_stride + f0;
+    const int32_t* off = a.cfreq ? nullptr : a.offsets + (size_t)h * a.off_stride + f0;
     double w[kPer];
     int c = 0;
     double mx = 0.0;
@@ -131,7 +138,7 @@ __global__ __launch_bounds__(kPrepThreads) void sc_prep_kernel(ScoreArgs a) {
         if (i < nf) {
             const unsigned long long sacc = tbl[i];
             if (sacc) {
-                const int freq = off[i + 1] - off[i];
+                const int freq = a.cfreq ? a.cfreq[(size_t)h * a.n_feat + f0 + i] : off[i + 1] - off[i];
                 if (freq > 0 && !(a.max_freq > 0 && freq > a.max_freq))
                     w[j] = (double)sacc * inv / ((double)logf(1.0f + (float)freq) + 1.0);
             }
@@ -196,7 +203,7 @@ __device__ __forceinline__ int lower_bound_pos(const int32_t* pos, int b, int e,
     return b + c;
 }
 
-template <int G>
+template <int G, bool CMP>
 __global__ __launch_bounds__(kScatterThreads) void sc_scatter_lds_kernel(ScoreArgs a) {
     extern __shared__ unsigned long long sblk[];
     __shared__ unsigned long long wmx[kScatterThreads / 64];
@@ -224,9 +231,15 @@ __global__ __launch_bounds__(kScatterThreads) void sc_scatter_lds_kernel(ScoreAr
     const int h0 = blockIdx.y * a.heads_per, h1 = min(a.n_heads, h0 + a.heads_per);
     for (int hr = h0 * a.nr; hr < h1 * a.nr; ++hr) {
         const int h = hr / a.nr, r = hr - h * a.nr;
-        const int32_t* pos = a.positions + (size_t)h * a.pos_stride;
-        const int32_t* off = a.offsets + (size_t)h * a.off_stride;
-        const int32_t* tab = a.btab ? a.btab + (size_t)h * a.n_feat * nbk : nullptr;
+        // compact index: 16-bit offsets from the block's start, the block's segments one after the other
+        using Posting = typename std::conditional<CMP, uint16_t, int32_t>::type;
+        const Posting* pos = CMP ? (const Posting*)(a.delta + (size_t)h * a.delta_stride)
+                                 : (const Posting*)(a.positions + (size_t)h * a.pos_stride);
+        const int32_t* off = CMP ? a.cstart + (size_t)h * a.cstart_stride + (size_t)blk * a.n_feat
+                                 : a.offsets + (size_t)h * a.off_stride;
+        const int32_t* tab = !CMP && a.btab ? a.btab + (size_t)h * a.n_feat * nbk : nullptr;
+        const unsigned pbase = CMP ? 0u : (unsigned)p0;           // what a stored posting is relative to
+        const bool cmp_empty = CMP && blk >= a.nblk;              // the compact index holds nothing beyond its blocks
         const ActiveList* act = a.act + (size_t)h * a.n_feat + (size_t)r * kRange;
         const int n_act = a.nact[hr];
         constexpr int kStep = (kScatterThreads / 64) * 64;
@@ -242,7 +255,12 @@ __global__ __launch_bounds__(kScatterThreads) void sc_scatter_lds_kernel(ScoreAr
                 wf = (unsigned long long)llrint(lw * scale);
                 if (wf) {
                     const int f = (int)raw.z;
-                    if (a.npb == 1) {
+                    if (CMP) {
+                        if (!cmp_empty) {
+                            b = off[f];
+                            e = off[f + 1];
+                        }
+                    } else if (a.npb == 1) {
                         b = off[f];
                         e = off[f + 1];
                     } else if (tab) {         // blocks at or beyond the table's end hold nothing
@@ -255,8 +273,9 @@ __global__ __launch_bounds__(kScatterThreads) void sc_scatter_lds_kernel(ScoreAr
                         b = off[f];
                         e = off[f + 1];
                         if (a.sorted && e - b > kNarrowMin) {      // the first and the last block need one search
-                            if (blk > 0) b = lower_bound_pos(pos, b, e, p0);
-                            if (blk < a.npb - 1) e = lower_bound_pos(pos, b, e, p1);
+                            const int32_t* pl = a.positions + (size_t)h * a.pos_stride;
+                            if (blk > 0) b = lower_bound_pos(pl, b, e, p0);
+                            if (blk < a.npb - 1) e = lower_bound_pos(pl, b, e, p1);
                         }
                     }
                 }
@@ -272,17 +291,17 @@ __global__ __launch_bounds__(kScatterThreads) void sc_scatter_lds_kernel(ScoreAr
                 const int sb = __builtin_amdgcn_readlane(b, src), sn = __builtin_amdgcn_readlane(n, src);
                 const unsigned long long w = ((unsigned long long)(unsigned)__builtin_amdgcn_readlane((int)(unsigned)(wf >> 32), src) << 32) |
                                              (unsigned)__builtin_amdgcn_readlane((int)(unsigned)wf, src);
-                const int32_t* lp = pos + sb;                              // uniform base, lanes add a 32-bit offset
+                const Posting* lp = pos + sb;                              // uniform base, lanes add a 32-bit offset
                 for (int c0 = 0; c0 < sn; c0 += 64 * kLong) {
                     int32_t pq[kLong];
 #pragma unroll
                     for (int u = 0; u < kLong; ++u) {
                         const int q = c0 + u * 64 + lane;
-                        pq[u] = q < sn ? lp[q] : -1;
+                        pq[u] = q < sn ? (int32_t)lp[q] : -1;
                     }
 #pragma unroll
                     for (int u = 0; u < kLong; ++u) {
-                        const unsigned rr = (unsigned)pq[u] - (unsigned)p0;
+                        const unsigned rr = (unsigned)pq[u] - pbase;
                         if (pq[u] >= 0 && rr < span) atomicAdd(&sblk[rr], w);
                     }
                 }
@@ -313,11 +332,11 @@ __global__ __launch_bounds__(kScatterThreads) void sc_scatter_lds_kernel(ScoreAr
 #pragma unroll
                     for (int u = 0; u < kShortSlots; ++u) {
                         const int q = c * G + sub;
-                        pq[u] = q < rc[u].y ? pos[rc[u].x + q] : -1;
+                        pq[u] = q < rc[u].y ? (int32_t)pos[rc[u].x + q] : -1;
                     }
 #pragma unroll
                     for (int u = 0; u < kShortSlots; ++u) {
-                        const unsigned rr = (unsigned)pq[u] - (unsigned)p0;
+                        const unsigned rr = (unsigned)pq[u] - pbase;
                         const unsigned long long w = ((unsigned long long)(unsigned)rc[u].w << 32) | (unsigned)rc[u].z;
                         if (pq[u] >= 0 && rr < span) atomicAdd(&sblk[rr], w);
                     }
@@ -586,37 +605,35 @@ Layout layout(int n_heads, int n_feat, int64_t L) {
     return l;
 }
 
-}  // namespace
+// What a scoring call reads from: the plain index (CSR + block table) or the compact one.
+struct ScoreSource {
+    int n_heads, n_feat, k;
+    int64_t tokens;
+    bool sorted;
+    const int32_t* offsets = nullptr; const int32_t* positions = nullptr; int64_t off_stride = 0, pos_stride = 0;
+    const int32_t* btab = nullptr; int nblk = 1;
+    const uint16_t* delta = nullptr; const int32_t* cstart = nullptr; const int32_t* cfreq = nullptr;
+    int64_t delta_stride = 0, cstart_stride = 0;
+};
 
-extern "C" size_t s3_coactivate_score_workspace(const s3_index* idx, int64_t n_positions) {
-    if (!idx || n_positions < 1) return 0;
-    S3IndexView v;
-    s3_index_view(idx, &v);
-    return layout(v.n_heads, v.n_feat, n_positions).total;
-}
-
-extern "C" int s3_coactivate_score(const s3_index* idx, const int32_t* qids, const float* qvals, int nq,
-                                   int64_t n_positions, int span_len, int top_b, int32_t max_freq, int nms,
-                                   float* scores_out, int32_t* span_start, float* span_score, int32_t* n_found,
-                                   void* ws, size_t ws_bytes, void* stream) {
-    if (!idx || !span_start || !span_score || !n_found || !ws) return s3_fail(S3_EINVAL, "s3_coactivate_score: null pointer");
-    if (nq < 0 || (nq > 0 && (!qids || !qvals))) return s3_fail(S3_EINVAL, "s3_coactivate_score: bad query arrays");
+static int score_run(const char* who, const ScoreSource& v, const int32_t* qids, const float* qvals, int nq,
+                     int64_t n_positions, int span_len, int top_b, int32_t max_freq, int nms, float* scores_out,
+                     int32_t* span_start, float* span_score, int32_t* n_found, void* ws, size_t ws_bytes, void* stream) {
+    if (!span_start || !span_score || !n_found || !ws) return s3_fail(S3_EINVAL, "%s: null pointer", who);
+    if (nq < 0 || (nq > 0 && (!qids || !qvals))) return s3_fail(S3_EINVAL, "%s: bad query arrays", who);
     if (span_len < 1 || top_b < 1 || top_b > 1024)
-        return s3_fail(S3_EINVAL, "s3_coactivate_score: span_len %d (>= 1) / top_b %d (1..1024) out of range", span_len, top_b);
+        return s3_fail(S3_EINVAL, "%s: span_len %d (>= 1) / top_b %d (1..1024) out of range", who, span_len, top_b);
     if (n_positions < 1 || n_positions >= (1LL << 31))
-        return s3_fail(S3_EINVAL, "s3_coactivate_score: n_positions %lld out of range", (long long)n_positions);
-    S3IndexView v;
-    s3_index_view(idx, &v);
-    if (!v.finalized) return s3_fail(S3_ESTATE, "s3_coactivate_score: index not finalized");
+        return s3_fail(S3_EINVAL, "%s: n_positions %lld out of range", who, (long long)n_positions);
     ScoreArgs a;
     a.n_heads = v.n_heads; a.n_feat = v.n_feat; a.k = v.k;
     a.offsets = v.offsets; a.off_stride = v.off_stride; a.positions = v.positions; a.pos_stride = v.pos_stride;
-    a.btab = v.btab_valid ? v.btab : nullptr;
-    a.nblk = v.btab_valid ? v.nblk : 1;
-    if ((int64_t)nq * a.k > (1 << 20)) return s3_fail(S3_EINVAL, "s3_coactivate_score: nq * k %lld > 2^20", (long long)nq * a.k);
+    a.btab = v.btab; a.nblk = v.nblk;
+    a.delta = v.delta; a.cstart = v.cstart; a.cfreq = v.cfreq; a.delta_stride = v.delta_stride; a.cstart_stride = v.cstart_stride;
+    if ((int64_t)nq * a.k > (1 << 20)) return s3_fail(S3_EINVAL, "%s: nq * k %lld > 2^20", who, (long long)nq * a.k);
     const Layout l = layout(a.n_heads, a.n_feat, n_positions);
-    if (ws_bytes < l.total) return s3_fail(S3_ECAPACITY, "s3_coactivate_score: workspace %zu < %zu bytes", ws_bytes, l.total);
-    if ((uintptr_t)ws & 255) return s3_fail(S3_EINVAL, "s3_coactivate_score: workspace must be 256-byte aligned");
+    if (ws_bytes < l.total) return s3_fail(S3_ECAPACITY, "%s: workspace %zu < %zu bytes", who, ws_bytes, l.total);
+    if ((uintptr_t)ws & 255) return s3_fail(S3_EINVAL, "%s: workspace must be 256-byte aligned", who);
 
     char* base = (char*)ws;
     a.qids = qids; a.qvals = qvals; a.nq = nq;
@@ -628,8 +645,8 @@ extern "C" int s3_coactivate_score(const s3_index* idx, const int32_t* qids, con
     // positions; four more bits are spare.  Weights keep 62 - hb significant bits below the largest one.
     a.hb = s3_ceil_log2((unsigned)(a.n_heads * a.k)) + s3_ceil_log2((unsigned)a.len) + 4;
     if (a.hb > 40)
-        return s3_fail(S3_EINVAL, "s3_coactivate_score: n_heads * k * span_len too large for the 64-bit fixed-point sums "
-                                  "(log2 of it, rounded up per factor, must be <= 36)");
+        return s3_fail(S3_EINVAL, "%s: n_heads * k * span_len too large for the 64-bit fixed-point sums "
+                                  "(log2 of it, rounded up per factor, must be <= 36)", who);
     a.nr = l.nr;
     a.wmax = (unsigned long long*)(base + l.wmax);
     a.nact = (int*)(base + l.nact);
@@ -644,15 +661,16 @@ extern "C" int s3_coactivate_score(const s3_index* idx, const int32_t* qids, con
     a.scores_out = scores_out; a.span_start = span_start; a.span_score = span_score; a.n_found = n_found;
 
     hipStream_t st = (hipStream_t)stream;
-    static S3LdsOnce once_prep, once_scatter[2];
+    static S3LdsOnce once_prep, once_scatter[4];
     const int prep_lds = (a.n_feat < kRange ? a.n_feat : kRange) * 8;
     if (int rc = s3_allow_lds(once_prep, (const void*)sc_prep_kernel, kRange * 8)) return rc;
     // lanes per short segment: from the mean length of a list's part in one position block
     const double mean_seg = (double)v.tokens * a.k / ((double)a.n_feat * l.npb);
-    const bool narrow = mean_seg <= 20.0;
-    auto scatter = narrow ? sc_scatter_lds_kernel<16> : sc_scatter_lds_kernel<32>;
-    if (int rc = s3_allow_lds(once_scatter[narrow], (const void*)scatter, kMaxPB * 8)) return rc;
-    // five launches: query weights, gather, sum of the head groups, pooling + tile maxima, Top-B
+    const bool narrow = mean_seg <= 20.0, cmp = v.delta != nullptr;
+    auto scatter = cmp ? (narrow ? sc_scatter_lds_kernel<16, true> : sc_scatter_lds_kernel<32, true>)
+                       : (narrow ? sc_scatter_lds_kernel<16, false> : sc_scatter_lds_kernel<32, false>);
+    if (int rc = s3_allow_lds(once_scatter[2 * cmp + narrow], (const void*)scatter, kMaxPB * 8)) return rc;
+    // at most five launches: query weights, gather, sum of the head groups, pooling + tile maxima, Top-B
     hipLaunchKernelGGL(sc_prep_kernel, dim3((unsigned)a.nr, (unsigned)a.n_heads), dim3(kPrepThreads), (size_t)prep_lds, st, a);
     hipLaunchKernelGGL(scatter, dim3((unsigned)a.npb, (unsigned)a.ngroup), dim3(kScatterThreads), (size_t)a.pb * 8, st, a);
     if (a.ngroup > 1) hipLaunchKernelGGL(sc_reduce_kernel, dim3((unsigned)((a.L + 63) / 64)), dim3(256), 0, st, a);
@@ -666,4 +684,53 @@ extern "C" int s3_coactivate_score(const s3_index* idx, const int32_t* qids, con
     hipLaunchKernelGGL(sc_topb_kernel, dim3(1), dim3(kTopThreads), 0, st, a);
     S3_HIP(hipGetLastError());
     return S3_OK;
+}
+
+}  // namespace
+
+extern "C" size_t s3_coactivate_score_workspace(const s3_index* idx, int64_t n_positions) {
+    if (!idx || n_positions < 1) return 0;
+    S3IndexView v;
+    s3_index_view(idx, &v);
+    return layout(v.n_heads, v.n_feat, n_positions).total;
+}
+
+extern "C" int s3_coactivate_score(const s3_index* idx, const int32_t* qids, const float* qvals, int nq,
+                                   int64_t n_positions, int span_len, int top_b, int32_t max_freq, int nms,
+                                   float* scores_out, int32_t* span_start, float* span_score, int32_t* n_found,
+                                   void* ws, size_t ws_bytes, void* stream) {
+    if (!idx) return s3_fail(S3_EINVAL, "s3_coactivate_score: null pointer");
+    S3IndexView v;
+    s3_index_view(idx, &v);
+    if (!v.finalized) return s3_fail(S3_ESTATE, "s3_coactivate_score: index not finalized");
+    ScoreSource src;
+    src.n_heads = v.n_heads; src.n_feat = v.n_feat; src.k = v.k; src.tokens = v.tokens; src.sorted = v.sorted;
+    src.offsets = v.offsets; src.off_stride = v.off_stride; src.positions = v.positions; src.pos_stride = v.pos_stride;
+    src.btab = v.btab_valid ? v.btab : nullptr;
+    src.nblk = v.btab_valid ? v.nblk : 1;
+    return score_run("s3_coactivate_score", src, qids, qvals, nq, n_positions, span_len, top_b, max_freq, nms, scores_out,
+                     span_start, span_score, n_found, ws, ws_bytes, stream);
+}
+
+extern "C" size_t s3_coactivate_score_compact_workspace(const s3_cindex* cidx, int64_t n_positions) {
+    if (!cidx || n_positions < 1) return 0;
+    S3CompactView c;
+    s3_cindex_view(cidx, &c);
+    return layout(c.n_heads, c.n_feat, n_positions).total;
+}
+
+extern "C" int s3_coactivate_score_compact(const s3_cindex* cidx, const int32_t* qids, const float* qvals, int nq,
+                                           int64_t n_positions, int span_len, int top_b, int32_t max_freq, int nms,
+                                           float* scores_out, int32_t* span_start, float* span_score, int32_t* n_found,
+                                           void* ws, size_t ws_bytes, void* stream) {
+    if (!cidx) return s3_fail(S3_EINVAL, "s3_coactivate_score_compact: null pointer");
+    S3CompactView c;
+    s3_cindex_view(cidx, &c);
+    ScoreSource src;
+    src.n_heads = c.n_heads; src.n_feat = c.n_feat; src.k = c.k; src.tokens = c.tokens; src.sorted = true;
+    src.nblk = c.nblk;
+    src.delta = c.delta; src.cstart = c.cstart; src.cfreq = c.cfreq; src.delta_stride = c.delta_stride;
+    src.cstart_stride = c.cstart_stride;
+    return score_run("s3_coactivate_score_compact", src, qids, qvals, nq, n_positions, span_len, top_b, max_freq, nms,
+                     scores_out, span_start, span_score, n_found, ws, ws_bytes, stream);
 }
