@@ -170,12 +170,13 @@ __global__ __launch_bounds__(kPrepThreads) void sc_prep_kernel(ScoreArgs a) {
 // is one head group, else into that group's partial array (summed by sc_reduce_kernel).  No global atomics.
 // A wavefront takes 64 lists at a time: lane l fetches weight and feature of list l and the part of the list that
 // lies in the block (its segment) -- from the index's block table when there is one; else, for lists sorted by
-// position, by a search; else the whole list, every posting filtered.  Segments of more than 2 G postings are then
-// walked one at a time by the whole wavefront, the others G lanes per segment (64 / G segments per load
-// instruction); G is 16 or 32, picked on the host from the mean segment length.
+// position, by a search; else the whole list, every posting filtered.  Postings are read as aligned 16-byte vectors
+// (what a wavefront keeps in flight bounds the rate: the gather is latency-bound).  Segments of more than 2 G
+// vectors are walked one at a time by the whole wavefront, the others G lanes per segment (64 / G segments per load
+// instruction); G is picked on the host from the mean segment length.
 constexpr int kScatterThreads = 1024;
-constexpr int kLong = 8;             // loads in flight while a long segment is walked by the whole wavefront
-constexpr int kShortSlots = 8;       // loads in flight while short segments are walked by lane groups
+constexpr int kLong = 4;             // 16-byte loads per lane in flight while a long segment is walked by the whole wavefront
+constexpr int kShortSlots = 4;       // 16-byte loads per lane in flight while short segments are walked by lane groups
 constexpr int kNarrowMin = 128;      // sorted lists longer than this are narrowed to the position block by search
 constexpr int kMaxPB = 1 << kS3PosBlockLog2;
 
@@ -201,6 +202,14 @@ __device__ __forceinline__ int lower_bound_pos(const int32_t* pos, int b, int e,
 #pragma unroll
     for (int u = 0; u < 8; ++u) c += (b + u < e && (int64_t)v[u] < key) ? 1 : 0;
     return b + c;
+}
+
+// element j of a 16-byte vector of postings (int32: 4 per vector; uint16: 8), as an unsigned position value
+template <typename Posting>
+__device__ __forceinline__ unsigned vec_posting(const uint4& v, int j) {
+    const unsigned w[4] = {v.x, v.y, v.z, v.w};
+    if (sizeof(Posting) == 4) return w[j];
+    return (w[j >> 1] >> ((j & 1) * 16)) & 0xFFFFu;
 }
 
 template <int G, bool CMP>
@@ -283,34 +292,46 @@ __global__ __launch_bounds__(kScatterThreads) void sc_scatter_lds_kernel(ScoreAr
             // this batch's segments (the part of each list that lies in the block) go to the wavefront's records
             const int n = wf ? max(e - b, 0) : 0;
             recs[lane] = make_int4(b, n, (int)(unsigned)wf, (int)(unsigned)(wf >> 32));
-            // long segments: one at a time, the whole wavefront, kLong loads in flight
-            unsigned long long ml = __ballot(n > 2 * G);
+            // Every load is an aligned 16-byte vector (EPV postings): a segment is read from the 16-byte boundary
+            // at or before its first posting, and the elements in front of it and behind its end are masked out
+            // (they lie in the same 16 bytes as a posting of the array, hence inside the array's allocation).
+            constexpr int EPV = 16 / (int)sizeof(Posting);
+            const int nv = n ? (int)(((((uintptr_t)(pos + b)) & 15) / sizeof(Posting) + n + EPV - 1) / EPV) : 0;
+            // long segments (more than 2 G vectors): one at a time, the whole wavefront, kLong vectors in flight per lane
+            unsigned long long ml = __ballot(nv > 2 * G);
             while (ml) {
                 const int src = (int)__builtin_ctzll(ml);
                 ml &= ml - 1;
                 const int sb = __builtin_amdgcn_readlane(b, src), sn = __builtin_amdgcn_readlane(n, src);
                 const unsigned long long w = ((unsigned long long)(unsigned)__builtin_amdgcn_readlane((int)(unsigned)(wf >> 32), src) << 32) |
                                              (unsigned)__builtin_amdgcn_readlane((int)(unsigned)wf, src);
-                const Posting* lp = pos + sb;                              // uniform base, lanes add a 32-bit offset
-                for (int c0 = 0; c0 < sn; c0 += 64 * kLong) {
-                    int32_t pq[kLong];
+                const uintptr_t addr = (uintptr_t)(pos + sb);                       // uniform
+                const int shift = (int)((addr & 15) / sizeof(Posting));
+                const uint4* vp = (const uint4*)(addr & ~(uintptr_t)15);
+                const int total = shift + sn, nvec = (total + EPV - 1) / EPV;
+                for (int v0 = 0; v0 < nvec; v0 += 64 * kLong) {
+                    uint4 raw[kLong];
 #pragma unroll
                     for (int u = 0; u < kLong; ++u) {
-                        const int q = c0 + u * 64 + lane;
-                        pq[u] = q < sn ? (int32_t)lp[q] : -1;
+                        const int vi = v0 + u * 64 + lane;
+                        raw[u] = vi < nvec ? vp[vi] : make_uint4(0, 0, 0, 0);
                     }
 #pragma unroll
                     for (int u = 0; u < kLong; ++u) {
-                        const unsigned rr = (unsigned)pq[u] - pbase;
-                        if (pq[u] >= 0 && rr < span) atomicAdd(&sblk[rr], w);
+                        const int el0 = (v0 + u * 64 + lane) * EPV;
+#pragma unroll
+                        for (int j = 0; j < EPV; ++j) {
+                            const unsigned rr = vec_posting<Posting>(raw[u], j) - pbase;
+                            if (el0 + j >= shift && el0 + j < total && rr < span) atomicAdd(&sblk[rr], w);
+                        }
                     }
                 }
             }
-            // short segments (at most 2 G postings): G lanes per segment, 64 / G segments per load instruction,
-            // kShortSlots load instructions in flight
+            // short segments: G lanes per segment (one vector each, two rounds if needed), 64 / G segments per load
+            // instruction, kShortSlots load instructions in flight
             constexpr int LPS = 64 / G;
             const int grp = lane / G, sub = lane % G;
-            unsigned long long ms = __ballot(n > 0 && n <= 2 * G);
+            unsigned long long ms = __ballot(nv > 0 && nv <= 2 * G);
             while (ms) {
                 int4 rc[kShortSlots];
                 bool two = false;
@@ -324,21 +345,32 @@ __global__ __launch_bounds__(kScatterThreads) void sc_scatter_lds_kernel(ScoreAr
                         idx = grp == g ? sbit : idx;
                     }
                     rc[u] = idx >= 0 ? recs[idx] : make_int4(0, 0, 0, 0);
-                    two = two || rc[u].y > G;
+                }
+                const uint4* vp[kShortSlots];
+                int shift[kShortSlots], total[kShortSlots];
+#pragma unroll
+                for (int u = 0; u < kShortSlots; ++u) {
+                    const uintptr_t addr = (uintptr_t)(pos + rc[u].x);
+                    shift[u] = (int)((addr & 15) / sizeof(Posting));
+                    vp[u] = (const uint4*)(addr & ~(uintptr_t)15);
+                    total[u] = rc[u].y ? shift[u] + rc[u].y : 0;
+                    two = two || total[u] > G * EPV;
                 }
                 const int chunks = __any(two) ? 2 : 1;
                 for (int c = 0; c < chunks; ++c) {
-                    int32_t pq[kShortSlots];
+                    uint4 raw[kShortSlots];
+#pragma unroll
+                    for (int u = 0; u < kShortSlots; ++u)
+                        raw[u] = (c * G + sub) * EPV < total[u] ? vp[u][c * G + sub] : make_uint4(0, 0, 0, 0);
 #pragma unroll
                     for (int u = 0; u < kShortSlots; ++u) {
-                        const int q = c * G + sub;
-                        pq[u] = q < rc[u].y ? (int32_t)pos[rc[u].x + q] : -1;
-                    }
-#pragma unroll
-                    for (int u = 0; u < kShortSlots; ++u) {
-                        const unsigned rr = (unsigned)pq[u] - pbase;
                         const unsigned long long w = ((unsigned long long)(unsigned)rc[u].w << 32) | (unsigned)rc[u].z;
-                        if (pq[u] >= 0 && rr < span) atomicAdd(&sblk[rr], w);
+                        const int el0 = (c * G + sub) * EPV;
+#pragma unroll
+                        for (int j = 0; j < EPV; ++j) {
+                            const unsigned rr = vec_posting<Posting>(raw[u], j) - pbase;
+                            if (el0 + j >= shift[u] && el0 + j < total[u] && rr < span) atomicAdd(&sblk[rr], w);
+                        }
                     }
                 }
             }
@@ -667,8 +699,8 @@ static int score_run(const char* who, const ScoreSource& v, const int32_t* qids,
     // lanes per short segment: from the mean length of a list's part in one position block
     const double mean_seg = (double)v.tokens * a.k / ((double)a.n_feat * l.npb);
     const bool narrow = mean_seg <= 20.0, cmp = v.delta != nullptr;
-    auto scatter = cmp ? (narrow ? sc_scatter_lds_kernel<16, true> : sc_scatter_lds_kernel<32, true>)
-                       : (narrow ? sc_scatter_lds_kernel<16, false> : sc_scatter_lds_kernel<32, false>);
+    auto scatter = cmp ? (narrow ? sc_scatter_lds_kernel<4, true> : sc_scatter_lds_kernel<8, true>)
+                       : (narrow ? sc_scatter_lds_kernel<8, false> : sc_scatter_lds_kernel<16, false>);
     if (int rc = s3_allow_lds(once_scatter[2 * cmp + narrow], (const void*)scatter, kMaxPB * 8)) return rc;
     // at most five launches: query weights, gather, sum of the head groups, pooling + tile maxima, Top-B
     hipLaunchKernelGGL(sc_prep_kernel, dim3((unsigned)a.nr, (unsigned)a.n_heads), dim3(kPrepThreads), (size_t)prep_lds, st, a);
