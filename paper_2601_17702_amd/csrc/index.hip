@@ -335,8 +335,13 @@ __global__ __launch_bounds__(kSplitThreads, kSplitOcc) void idx_bucket_sort_kern
         unsigned meta[kSplitRounds];       // split_round()
 #pragma unroll
         for (int r = 0; r < kSplitRounds; ++r) {
+            if (r * 64 >= seg) {          // uniform: this round is past the wavefront's share
+                meta[r] = 0u;
+                pos[r] = 0;
+                continue;
+            }
             const int i = wave * seg + r * 64 + lane;
-            const uint32_t e = (r * 64 < seg && i < n_r) ? bufa[i] : 0u;
+            const uint32_t e = i < n_r ? bufa[i] : 0u;
             meta[r] = e;
             // all loads in flight at once; used only after the scan (row 0 if idle)
             pos[r] = d.pos_affine ? d.pos0 + (int32_t)(e >> d.S) : d.pos_log[e >> d.S];
@@ -356,7 +361,7 @@ __global__ __launch_bounds__(kSplitThreads, kSplitOcc) void idx_bucket_sort_kern
         if (multi) {
 #pragma unroll
             for (int r = 0; r < kSplitRounds; ++r)
-                if (meta[r] & kSplitValid) {
+                if (r * 64 < seg && (meta[r] & kSplitValid)) {
                     const unsigned fl = meta[r] & 0xFFu;
                     const int i = split_rank(row, meta[r]);
                     posout[cursor[fl] + (i - rstart[fl])] = pos[r];
@@ -366,7 +371,7 @@ __global__ __launch_bounds__(kSplitThreads, kSplitOcc) void idx_bucket_sort_kern
             if (tid < nd) lstart[tid] = out_base + rstart[tid];
 #pragma unroll
             for (int r = 0; r < kSplitRounds; ++r)
-                if (meta[r] & kSplitValid) bufb[split_rank(row, meta[r])] = pos[r];
+                if (r * 64 < seg && (meta[r] & kSplitValid)) bufb[split_rank(row, meta[r])] = pos[r];
         }
         __syncthreads();
         if (nbk && tid < nfl && rcount[tid] > 0) {

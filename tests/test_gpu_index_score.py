@@ -307,3 +307,39 @@ def test_scoring_of_long_contexts(T):
     ix = gpu_index(ids, n_feat, chunks=[50_000] * (T // 50_000 + 1))
     S, W, st_o, sc_o = oracle_score(ids, qids, qvals, n_feat, T, 128, 16, 0, True)
     check_score(run_gpu_score(ix, qids, qvals, T, 128, 16, 0, True), S, W, st_o, sc_o, 128, True)
+
+
+def test_scoring_with_shifted_positions_and_index_reuse():
+    """Positions that start at an offset: inside the range the index's block table covers (table used), beyond it
+    (lists are searched instead), and the same index object reset and fed another stream (table rebuilt)."""
+    import torch
+    import paper_2601_17702_amd as s3
+    rng = np.random.default_rng(99)
+    H, T, k, n_feat, nq = 2, 20000, 8, 256, 10
+    ix = s3.Index(H, n_feat, k, 40000)                         # capacity: three blocks of 16384 positions
+    for base in (0, 12000, 30000, 5):                          # 30000 + 20000 lies beyond the three blocks
+        ids = np.stack([rand_ids(rng, T, k, n_feat, hot=3) for _ in range(H)])
+        qids = np.stack([rand_ids(rng, nq, k, n_feat) for _ in range(H)])
+        qids[:, 0, 0] = 3
+        qvals = rng.random((H, nq, k)).astype(np.float32)
+        ix.reset()
+        g = torch.from_numpy(ids).cuda()
+        for a in range(0, T, 3000):
+            ix.append(g[:, a:a + 3000].contiguous(), base_pos=base + a)
+        ix.finalize()
+        L = base + T + 7
+        pos = np.arange(base, base + T, dtype=np.int32)
+        for h in range(H):
+            _, (off_o, pos_o) = oracle_csr(ids[h], pos, n_feat)
+            assert_csr_equal(ix, h, off_o, pos_o)
+        S, W, st_o, sc_o = oracle_score(ids, qids, qvals, n_feat, L, 48, 8, 0, True, positions=pos)
+        check_score(run_gpu_score(ix, qids, qvals, L, 48, 8, 0, True), S, W, st_o, sc_o, 48, True)
+        if base + T <= 3 * 16384:                              # the compact form needs the table's range
+            cx = ix.compact(0)
+            st, sc, nf, Sg = cx.coactivate_score(torch.from_numpy(qids).cuda(), torch.from_numpy(qvals).cuda(), L, 48, 8,
+                                                 want_scores=True)
+            torch.cuda.synchronize()
+            check_score((st.cpu().numpy(), sc.cpu().numpy(), int(nf.item()), Sg.cpu().numpy()), S, W, st_o, sc_o, 48, True)
+        else:
+            with pytest.raises(s3.S3Error):
+                ix.compact(0)
