@@ -35,7 +35,7 @@ enum {
 
 enum { S3_BF16 = 0, S3_FP32 = 1 };
 
-#define S3_MAX_K 64          /* largest supported Top-k */
+#define S3_MAX_K 128         /* largest supported Top-k */
 #define S3_MAX_FEAT 65536    /* largest supported SAE width */
 
 /* Message of the last error on this host thread (valid until the next failing call). */
@@ -57,9 +57,12 @@ const char* s3_last_error(void);
  * row always has exactly k distinct ids; vals = max(z, 0).  Within a row the order is
  * (z descending, id ascending).  z is accumulated in fp32 and never written to memory.
  * Inputs are assumed finite.
- * Limits: d_head in {64, 128, 256}; 1 <= k <= min(n_feat, S3_MAX_K), and k <= 62 for fp32 with
- * d_head 256 (the candidate lists of that kernel would not fit the 160 KB of LDS);
- * n_feat <= S3_MAX_FEAT; T >= 0 (T == 0 is a no-op); n_heads >= 1.  Otherwise S3_EINVAL.
+ * Limits: d_head in {64, 128, 256}; 1 <= k <= min(n_feat, S3_MAX_K); the candidate lists must
+ * fit the 160 KB of LDS beside two 32-feature tiles of W_enc, which leaves k <= 128 for bf16 with
+ * d_head <= 128 and fp32 with d_head 64, k <= 121 for bf16 with d_head 256 and fp32 with d_head
+ * 128, k <= 78 for fp32 with d_head 256 (k = 128 is the sparsity the paper trains its SAEs with,
+ * App. B.3); n_feat <= S3_MAX_FEAT; T >= 0 (T == 0 is a no-op); n_heads >= 1.  Otherwise S3_EINVAL.
+ * bf16 with d_head 128, k <= 64 and n_feat a multiple of 128 takes the fast kernel.
  * No workspace is needed (so there is no workspace query for this call).
  */
 int s3_sae_encode_topk(const void* x, int dtype, int T, int d_head, const void* w_enc,
@@ -98,6 +101,9 @@ int s3_sae_encode_topk_stream(const void* x, int dtype, int T, int d_head, const
  * s3_index_create allocates everything for n_heads independent indexes of up to max_tokens
  * tokens each (host call; the handle is library-owned; destroy with s3_index_destroy).
  * Limits: n_feat <= S3_MAX_FEAT, k <= S3_MAX_K, max_tokens * k < 2^31, max_tokens <= 2^24.
+ * Beside the CSR the index holds the intermediate of the build (4 bytes per posting) and, for up
+ * to 64 blocks of 16384 tokens, a table of where every block starts in every list
+ * (4 * n_feat * (blocks - 1) bytes per head), which scoring reads instead of searching the lists.
  */
 typedef struct s3_index s3_index;
 int s3_index_create(int n_heads, int n_feat, int k, int64_t max_tokens, s3_index** out);

@@ -14,7 +14,7 @@ LIB_PATH = os.path.join(_HERE, "libs3attn.so")
 _lib = None
 
 S3_BF16, S3_FP32 = 0, 1
-MAX_K, MAX_FEAT = 64, 65536
+MAX_K, MAX_FEAT = 128, 65536
 
 
 class S3Error(RuntimeError):

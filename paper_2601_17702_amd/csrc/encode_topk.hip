@@ -228,7 +228,7 @@ __global__ __launch_bounds__(kThreads) void sae_encode_topk_kernel(EncParams p) 
     int cnt = 0;
     float tau = p.ablate ? INFINITY : -INFINITY;
     const int k = p.k;
-    const int loose = k + (k >> 3) + 2;
+    const int loose = min(k + (k >> 3) + 2, p.capt - p.headroom);
 
     const int ntiles = (p.n_feat + kFT - 1) / kFT;
     uint4 wreg[NV];
@@ -263,9 +263,10 @@ __global__ __launch_bounds__(kThreads) void sae_encode_topk_kernel(EncParams p) 
         const int cur = j & 1;
         if (j + 1 < ntiles) gload(j + 1);
 
-        {   // make room: worst case every accumulator of the tile is appended (16 per lane)
+        {   // make room: worst case every accumulator of the tile (headroom 32) or of its first half (headroom 16,
+            // used for k > 64 where LDS is short) is appended: 16 or 8 per lane, two lanes per token
             int used = cnt + __shfl_xor(cnt, 32);
-            if (__any(used > p.capt - kHeadroom)) refresh(c, k, loose, cnt, tau);
+            if (__any(used > p.capt - p.headroom)) refresh(c, k, loose, cnt, tau);
         }
 
         f32x16 acc;
@@ -282,7 +283,24 @@ __global__ __launch_bounds__(kThreads) void sae_encode_topk_kernel(EncParams p) 
         const int fb = j * kFT + half * 4;
         int wp = c.base + cnt * c.step;
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
+        for (int r = 0; r < 8; ++r) {
+            float v = acc[r];
+            if (v > tau) {
+                c.cv[wp] = v;
+                c.ci[wp] = (uint16_t)(fb + (r >> 2) * 8 + (r & 3));
+                wp += c.step;
+                ++cnt;
+            }
+        }
+        {   // room for the second half (never short when the tile started with 32 free slots)
+            int used = cnt + __shfl_xor(cnt, 32);
+            if (__any(used > p.capt - 16)) {
+                refresh(c, k, loose, cnt, tau);
+                wp = c.base + cnt * c.step;
+            }
+        }
+#pragma unroll
+        for (int r = 8; r < 16; ++r) {
             float v = acc[r];
             if (v > tau) {
                 c.cv[wp] = v;
@@ -305,25 +323,28 @@ __global__ __launch_bounds__(kThreads) void sae_encode_topk_kernel(EncParams p) 
         if (tok0 + nn >= p.T) break;
         const int clo = __builtin_amdgcn_readfirstlane(__shfl(cnt, nn));
         const int chi = __builtin_amdgcn_readfirstlane(__shfl(cnt, nn + 32));
-        const bool mine = lane < clo + chi;
-        const int slot = lane < clo ? lane : p.capt - 1 - (lane - clo);
-        float v = mine ? c.cv[slot * 32 + nn] : -INFINITY;
-        int id = mine ? (int)c.ci[slot * 32 + nn] : 0x7FFFFFFF;
-        int rank = 0;
-        for (int q = 0; q < clo; ++q) {
-            float vq = c.cv[q * 32 + nn];
-            int iq = c.ci[q * 32 + nn];
-            rank += (vq > v || (vq == v && iq < id)) ? 1 : 0;
-        }
-        for (int q = 0; q < chi; ++q) {
-            float vq = c.cv[(p.capt - 1 - q) * 32 + nn];
-            int iq = c.ci[(p.capt - 1 - q) * 32 + nn];
-            rank += (vq > v || (vq == v && iq < id)) ? 1 : 0;
-        }
-        if (mine && rank < k) {
-            size_t o = (size_t)(tok0 + nn) * k + rank;
-            ids_h[o] = id;
-            vals_h[o] = fmaxf(v, 0.f);
+        for (int c0 = 0; c0 < clo + chi; c0 += 64) {         // one candidate per lane, 64 at a time (k may exceed 64)
+            const int ci = c0 + lane;
+            const bool mine = ci < clo + chi;
+            const int slot = ci < clo ? ci : p.capt - 1 - (ci - clo);
+            float v = mine ? c.cv[slot * 32 + nn] : -INFINITY;
+            int id = mine ? (int)c.ci[slot * 32 + nn] : 0x7FFFFFFF;
+            int rank = 0;
+            for (int q = 0; q < clo; ++q) {
+                float vq = c.cv[q * 32 + nn];
+                int iq = c.ci[q * 32 + nn];
+                rank += (vq > v || (vq == v && iq < id)) ? 1 : 0;
+            }
+            for (int q = 0; q < chi; ++q) {
+                float vq = c.cv[(p.capt - 1 - q) * 32 + nn];
+                int iq = c.ci[(p.capt - 1 - q) * 32 + nn];
+                rank += (vq > v || (vq == v && iq < id)) ? 1 : 0;
+            }
+            if (mine && rank < k) {
+                size_t o = (size_t)(tok0 + nn) * k + rank;
+                ids_h[o] = id;
+                vals_h[o] = fmaxf(v, 0.f);
+            }
         }
     }
 }
@@ -385,11 +406,15 @@ static int encode_impl(const char* who, const void* x, int dtype, int T, int d_h
     if (fast)
         return tau_hint ? s3_encode_fast_stream(p, tau_hint, ws, st) : s3_encode_fast_launch(p, st);
     p.tiles_per_head = (T + kTokWG - 1) / kTokWG;
-    // list capacity per token: k survivors + headroom for one tile + room for new candidates between refreshes
-    int capt = k + kHeadroom + (k <= 32 ? 16 : 32);
+    // list capacity per token: k survivors + headroom for a run of appends + room for new candidates between refreshes;
+    // the headroom is a whole tile's worth (32) where that fits the LDS, else half a tile's (16, re-checked mid-tile)
+    const size_t fixed_lds = 2 * kFT * ((size_t)d_head * (dtype == S3_BF16 ? 2 : 4) + 16) + 2 * kFT * sizeof(float);
+    auto lists_fit = [&](int c) { return fixed_lds + (size_t)kWaves * c * 32 * 6 <= 160 * 1024; };
+    p.headroom = k <= 64 && lists_fit(k + kHeadroom + (k <= 32 ? 16 : 32)) ? kHeadroom : 16;
+    int capt = k + p.headroom + (k <= 32 ? 16 : 32);
 #ifdef S3_TUNING
     capt = env_int("S3_ENC_CAPT", capt);
-    if (capt < k + kHeadroom + 4 || capt > 512) return s3_fail(S3_EINVAL, "%s: bad S3_ENC_CAPT %d", who, capt);
+    if (capt < k + p.headroom + 4 || capt > 512) return s3_fail(S3_EINVAL, "%s: bad S3_ENC_CAPT %d", who, capt);
 #endif
     p.capt = capt;
 #define S3_CASE(DT, DH) if (dtype == DT && d_head == DH) return launch<DT, DH>(p, n_heads, st);

@@ -112,6 +112,7 @@ struct EncParams {
     int32_t* ids;
     float* vals;
     int T, n_feat, k, n_heads, capt, tiles_per_head;
+    int headroom;  // generic kernel: free list slots per token required before a run of appends (32, or 16 for k > 64)
     int ablate;    // tuning builds (-DS3_TUNING) only: parts of the kernel compiled out; always 0 in the product
     int soft;      // fast path: list length per lane that asks for a workgroup-wide refresh (0: off)
     // streamed calls (threshold carried from the previous chunk), fast path only

@@ -62,6 +62,10 @@ WORKLOADS = {
     "c3_long": Workload("c3_long", 32, 8, 131072, 4096, 128, 16384, 32, "bf16", 256, 64, 16, 2, "zipf"),
     # Qwen2.5-7B shape: 28 layers x 4 KV heads, 128 query tokens x 7 Q heads per KV head
     "c4_qwen7b": Workload("c4_qwen7b", 28, 4, 65536, 2048, 128, 32768, 64, "bf16", 896, 32, 32, 3, "lowrank"),
+    # the paper's own SAE setting (App. B.3: expansion 128 -> 16384 features for d_head 128, k = 128) on a
+    # Mistral-7B-like shape with four target layers (App. A, layer table): 4 layers x 8 KV heads, chunk 2048,
+    # N = 40 centres; 64 query tokens x 4 Q heads per KV head
+    "c6_paper_sae": Workload("c6_paper_sae", 4, 8, 32768, 2048, 128, 16384, 128, "bf16", 256, 48, 40, 5, "lowrank"),
     # wide SAE stress
     "c5_wide": Workload("c5_wide", 1, 8, 1048576, 8192, 128, 65536, 64, "bf16", 256, 128, 64, 4, "lowrank", 0.05),
 }

@@ -57,7 +57,7 @@ def test_host_side_argument_validation():
         L.s3_sae_encode_topk(None, 0, 8, 128, one, one, 64, 4, 1, one, one, None),        # null x
         L.s3_sae_encode_topk(one, 2, 8, 128, one, one, 64, 4, 1, one, one, None),         # dtype
         L.s3_sae_encode_topk(one, 0, 8, 96, one, one, 64, 4, 1, one, one, None),          # d_head
-        L.s3_sae_encode_topk(one, 0, 8, 128, one, one, 64, 65, 1, one, one, None),        # k > S3_MAX_K
+        L.s3_sae_encode_topk(one, 0, 8, 128, one, one, 256, 129, 1, one, one, None),      # k > S3_MAX_K
         L.s3_sae_encode_topk(one, 0, 8, 128, one, one, 16, 32, 1, one, one, None),        # k > n_feat
         L.s3_sae_encode_topk(one, 0, 8, 128, one, one, 70000, 4, 1, one, one, None),      # n_feat
         L.s3_sae_encode_topk(one, 0, -1, 128, one, one, 64, 4, 1, one, one, None),        # T
@@ -67,12 +67,12 @@ def test_host_side_argument_validation():
     assert b"s3_sae_encode_topk" in L.s3_last_error()
     h = C.c_void_p()
     assert L.s3_index_create(0, 64, 4, 10, C.byref(h)) == -1
-    assert L.s3_index_create(1, 64, 65, 10, C.byref(h)) == -1
+    assert L.s3_index_create(1, 256, 129, 10, C.byref(h)) == -1
     assert L.s3_index_create(1, 64, 4, 1 << 25, C.byref(h)) == -1
     assert L.s3_index_append(None, one, 1, None, 0, None) == -1
     assert L.s3_index_finalize(None, None) == -1
     assert L.s3_index_build(one, None, 8, 4, 64, one, one, one, 16, None) == -3          # workspace too small
-    assert L.s3_index_build_workspace(8, 4, 64) > 0 and L.s3_index_build_workspace(8, 65, 64) == 0
+    assert L.s3_index_build_workspace(8, 4, 64) > 0 and L.s3_index_build_workspace(8, 129, 256) == 0
     assert L.s3_coactivate_score(None, one, one, 1, 10, 4, 2, 0, 1, None, one, one, one, one, 1 << 20, None) == -1
     need = L.s3_sae_encode_topk_stream_workspace(2, 512)
     assert need >= 2 * 512 * 4 and L.s3_sae_encode_topk_stream_workspace(0, 512) == 0
@@ -82,4 +82,4 @@ def test_host_side_argument_validation():
     assert L.s3_sae_encode_topk_stream(*args, one, C.c_void_p(264), need, None) == -1      # workspace alignment
     assert L.s3_sae_encode_topk_stream(*args, one, one, need - 1, None) == -3              # workspace too small
     assert b"s3_sae_encode_topk_stream" in L.s3_last_error()
-    assert s3.MAX_K == 64 and s3.MAX_FEAT == 65536
+    assert s3.MAX_K == 128 and s3.MAX_FEAT == 65536

@@ -45,6 +45,11 @@ def test_workload_shapes_sampled(name, T, n_feat, heads):
     ("fp32", 256, 300, 33, 64),
     ("bf16", 128, 48, 48, 70),       # k == n_feat: every feature is returned
     ("fp32", 128, 64, 64, 1),        # single token
+    ("bf16", 128, 16384, 128, 200),  # the paper's SAE setting: expansion 128, k = 128 (App. B.3)
+    ("fp32", 64, 700, 128, 70),      # k = 128 in fp32
+    ("bf16", 256, 1024, 121, 40),    # the largest k that fits beside the 256-wide tiles
+    ("bf16", 128, 128, 128, 33),     # k == n_feat == 128
+    ("fp32", 256, 500, 78, 35),      # half-tile headroom below k = 64's usual setting (fp32, d_head 256)
 ])
 def test_odd_shapes(dtype, d, n_feat, k, T):
     rng = np.random.default_rng(d + n_feat + k + T)

@@ -103,7 +103,7 @@ def test_index_and_scores_full_size():
 # Every workload at its own size, in the launch configuration bench.py times: all (layer, head) pairs per call,
 # the workload's chunk length, the streamed encoder with thresholds carried from chunk to chunk, the index fed
 # chunk by chunk, the query encode and the scoring call with the workload's query count, span length and Top-B.
-FULL = ["c2_llama8b", "c3_long", "c4_qwen7b", "c5_wide"]
+FULL = ["c2_llama8b", "c3_long", "c4_qwen7b", "c5_wide", "c6_paper_sae"]
 
 
 def _sample_rows(rng, T, n):

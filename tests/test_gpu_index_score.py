@@ -60,7 +60,7 @@ def assert_csr_equal(ix, head, off_o, pos_o):
 
 @pytest.mark.parametrize("T,k,n_feat", [
     (1, 1, 1), (255, 16, 200), (256, 32, 1000), (257, 32, 16384), (1300, 64, 65536),
-    (5000, 48, 4096), (700, 7, 33),
+    (5000, 48, 4096), (700, 7, 33), (900, 128, 16384), (300, 100, 128),
 ])
 def test_index_bit_exact_vs_oracle(T, k, n_feat):
     rng = np.random.default_rng(T + k + n_feat)
@@ -190,6 +190,7 @@ def test_tiny_case_by_hand():
     (2, 1000, 4, 50, 6, 128, 64, 0, True),           # more spans asked for than disjoint windows exist
     (2, 1000, 4, 50, 6, 512, 4, 0, True),            # long windows over few heads: the windows' fixed-point sums need
     (1, 3000, 8, 16, 4, 2048, 2, 0, True),           # the span length in their headroom (frequent queried features)
+    (2, 1200, 128, 16384, 6, 48, 40, 0, True),       # k = 128 (the paper's SAE sparsity), 40 spans of 48 (App. B.3)
 ])
 def test_score_and_spans_vs_oracle(H, T, k, n_feat, nq, span_len, top_b, max_freq, nms):
     rng = np.random.default_rng(H * T + k + nq + span_len)
