@@ -43,6 +43,7 @@ struct IdxDev {
     int32_t* btab;            // [n_heads][n_feat][nblk - 1] block table for scoring, or null
     int64_t inter_stride, piece_stride, off_stride, pos_stride;
     int n_feat, k, S, NB, nbB, ptok, tile_post, max_tiles;
+    int w16;                  // intermediate entries are 16 bits: (row inside the tile) << S | f & mask (else 32 bits, row of the stream)
     int nblk;                 // position blocks the table covers
     int pos_affine;           // position of row r is pos0 + r (every append used contiguous implicit positions)
     int32_t pos0;
@@ -166,7 +167,7 @@ __global__ __launch_bounds__(kSplitThreads, kSplitOcc) void idx_partition_kernel
         const uint32_t id = valid ? word[r] : 0u;
         const uint32_t dg = min(id >> d.S, (uint32_t)(nd - 1));   // ids are < n_feat by contract; never index past the counters
         const uint32_t trow = __umulhi(i, d.kinv) + i * k_is_1;   // i / k (kinv is 0 when k == 1)
-        word[r] = ((row0 + trow) << d.S) | (id & mask);
+        word[r] = (((d.w16 ? 0u : row0) + trow) << d.S) | (id & mask);
         if (d.k >= kRowAtomicMinK) {
             // A token's ids are distinct, so entries of one feature never share a row: one returning LDS add per row
             // of the round (in row order; a wavefront's LDS operations execute in program order) ranks every entry
@@ -189,8 +190,14 @@ __global__ __launch_bounds__(kSplitThreads, kSplitOcc) void idx_partition_kernel
         if (meta[r] & kSplitValid) stage[split_rank(row, meta[r])] = word[r];
     }
     __syncthreads();
-    uint32_t* out = d.inter + (size_t)head * d.inter_stride + (size_t)tile * d.tile_post;
-    for (int i = tid; i < n; i += kSplitThreads) out[i] = stage[i];
+    const size_t at = (size_t)head * d.inter_stride + (size_t)tile * d.tile_post;
+    if (d.w16) {
+        uint16_t* out = (uint16_t*)d.inter + at;
+        for (int i = tid; i < n; i += kSplitThreads) out[i] = (uint16_t)stage[i];
+    } else {
+        uint32_t* out = d.inter + at;
+        for (int i = tid; i < n; i += kSplitThreads) out[i] = stage[i];
+    }
     uint32_t* pc = d.piece + (size_t)head * d.piece_stride;
     for (int b = tid; b < d.NB; b += kSplitThreads)
         pc[(size_t)b * d.max_tiles + tile] = ((uint32_t)bstart[b] << 16) | (uint32_t)bcount[b];
@@ -265,7 +272,8 @@ __global__ __launch_bounds__(kSplitThreads, kSplitOcc) void idx_bucket_sort_kern
         }
         return;
     }
-    const uint32_t* inter = d.inter + (size_t)head * d.inter_stride;
+    // entry i of the head's intermediate array (16-bit entries carry the row inside their tile: the caller adds the tile's first row)
+    const uint16_t* inter16 = (const uint16_t*)d.inter + (size_t)head * d.inter_stride;
     int32_t* posout = d.positions + (size_t)head * d.pos_stride;
     const bool multi = n_b > kSortCap || n_tiles > kSplitThreads;   // more than one round of pieces
 
@@ -276,8 +284,12 @@ __global__ __launch_bounds__(kSplitThreads, kSplitOcc) void idx_bucket_sort_kern
         for (int t = wave; t < n_tiles; t += kSplitWaves) {
             uint32_t p = pc[t];
             int c = (int)(p & 0xFFFFu);
-            const uint32_t* e = inter + (size_t)t * d.tile_post + (p >> 16);
-            for (int i = lane; i < c; i += 64) atomicAdd(&hist[e[i] & mask], 1);
+            const size_t e0 = (size_t)t * d.tile_post + (p >> 16);
+            if (d.w16) {
+                for (int i = lane; i < c; i += 64) atomicAdd(&hist[inter16[e0 + i] & mask], 1);
+            } else {
+                for (int i = lane; i < c; i += 64) atomicAdd(&hist[d.inter[(size_t)head * d.inter_stride + e0 + i] & mask], 1);
+            }
         }
         __syncthreads();
         int tot;
@@ -303,30 +315,42 @@ __global__ __launch_bounds__(kSplitThreads, kSplitOcc) void idx_bucket_sort_kern
         {
             const int hw = tid >> 5, l0 = tid & 31;
             for (int j0 = hw; j0 < m; j0 += 4 * (kSplitThreads / 32)) {
-                const uint32_t* sp[4];
+                size_t sp[4];                      // first entry of the piece in the head's intermediate array
                 int dst[4], cc[4];
-                uint32_t v[4], v2[4];
+                uint32_t v[4], v2[4], add[4];      // add: what turns a 16-bit entry into the 32-bit form (its tile's first row)
+                const uint32_t* in32 = d.inter + (size_t)head * d.inter_stride;
 #pragma unroll
                 for (int q = 0; q < 4; ++q) {
                     const int j = j0 + q * (kSplitThreads / 32);
                     const uint32_t pj = j < m ? pinfo[j] : 0u;
+                    const int tile = tp + (j < m ? j : 0);
                     cc[q] = (int)(pj & 0xFFFFu);
                     dst[q] = j < m ? pref[j] : 0;
-                    sp[q] = inter + (size_t)(tp + (j < m ? j : 0)) * d.tile_post + (pj >> 16);
+                    sp[q] = (size_t)tile * d.tile_post + (pj >> 16);
+                    add[q] = d.w16 ? ((uint32_t)tile * (uint32_t)d.ptok) << d.S : 0u;
                 }
+                if (d.w16) {
 #pragma unroll
-                for (int q = 0; q < 4; ++q) {      // the first 64 entries of each piece: eight loads in flight
-                    v[q] = l0 < cc[q] ? sp[q][l0] : 0u;
-                    v2[q] = l0 + 32 < cc[q] ? sp[q][l0 + 32] : 0u;
+                    for (int q = 0; q < 4; ++q) {  // the first 64 entries of each piece: eight loads in flight
+                        v[q] = l0 < cc[q] ? inter16[sp[q] + l0] : 0u;
+                        v2[q] = l0 + 32 < cc[q] ? inter16[sp[q] + l0 + 32] : 0u;
+                    }
+                } else {
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        v[q] = l0 < cc[q] ? in32[sp[q] + l0] : 0u;
+                        v2[q] = l0 + 32 < cc[q] ? in32[sp[q] + l0 + 32] : 0u;
+                    }
                 }
 #pragma unroll
                 for (int q = 0; q < 4; ++q) {
-                    if (l0 < cc[q]) bufa[dst[q] + l0] = v[q];
-                    if (l0 + 32 < cc[q]) bufa[dst[q] + l0 + 32] = v2[q];
+                    if (l0 < cc[q]) bufa[dst[q] + l0] = v[q] + add[q];
+                    if (l0 + 32 < cc[q]) bufa[dst[q] + l0 + 32] = v2[q] + add[q];
                 }
 #pragma unroll
                 for (int q = 0; q < 4; ++q)
-                    for (int l = l0 + 64; l < cc[q]; l += 32) bufa[dst[q] + l] = sp[q][l];
+                    for (int l = l0 + 64; l < cc[q]; l += 32)
+                        bufa[dst[q] + l] = (d.w16 ? (uint32_t)inter16[sp[q] + l] : in32[sp[q] + l]) + add[q];
             }
         }
         for (int i = tid; i < kSplitWaves * nd; i += kSplitThreads) cnt[i] = 0;
@@ -425,7 +449,7 @@ size_t bucket_sort_lds(int S) {
 }
 
 struct Geometry {
-    int S, NB, nbB, ptok, tile_post;
+    int S, NB, nbB, ptok, tile_post, w16;
 };
 
 bool geometry(int n_feat, int k, Geometry& g) {
@@ -436,6 +460,7 @@ bool geometry(int n_feat, int k, Geometry& g) {
     g.nbB = s3_ceil_log2((unsigned)g.NB);
     g.ptok = kTilePost / k;
     g.tile_post = g.ptok * k;
+    g.w16 = g.S + s3_ceil_log2((unsigned)g.ptok) <= 16;      // (row inside the tile, low feature bits) fit 16 bits
     return true;
 }
 
@@ -529,7 +554,7 @@ static int index_build_impl(const char* who, const int32_t* ids, const int32_t* 
     }
     char* base = (char*)ws;
     IdxDev d;
-    d.n_feat = n_feat; d.k = k; d.S = g.S; d.NB = g.NB; d.nbB = g.nbB; d.ptok = g.ptok; d.tile_post = g.tile_post;
+    d.n_feat = n_feat; d.k = k; d.S = g.S; d.NB = g.NB; d.nbB = g.nbB; d.ptok = g.ptok; d.tile_post = g.tile_post; d.w16 = g.w16;
     d.kinv = k > 1 ? (uint32_t)(((1ull << 32) + (uint32_t)k - 1) / (uint32_t)k) : 0u;
     d.max_tiles = (T + g.ptok - 1) / g.ptok;
     d.inter = (uint32_t*)(base + off[0]); d.piece = (uint32_t*)(base + off[1]);
@@ -583,7 +608,7 @@ int s3_index_create(int n_heads, int n_feat, int k, int64_t max_tokens, s3_index
     const int64_t nb = (max_tokens + (1 << kS3PosBlockLog2) - 1) >> kS3PosBlockLog2;
     ix->nblk = nb >= 2 && nb <= kS3MaxTableBlocks ? (int)nb : 0;
     IdxDev& d = ix->d;
-    d.n_feat = n_feat; d.k = k; d.S = g.S; d.NB = g.NB; d.nbB = g.nbB; d.ptok = g.ptok; d.tile_post = g.tile_post;
+    d.n_feat = n_feat; d.k = k; d.S = g.S; d.NB = g.NB; d.nbB = g.nbB; d.ptok = g.ptok; d.tile_post = g.tile_post; d.w16 = g.w16;
     d.kinv = k > 1 ? (uint32_t)(((1ull << 32) + (uint32_t)k - 1) / (uint32_t)k) : 0u;
     d.max_tiles = (int)((max_tokens + g.ptok - 1) / g.ptok);
     d.inter_stride = (int64_t)d.max_tiles * g.tile_post;
