@@ -298,8 +298,8 @@ def strided_ids(rng, T, k, n_feat):
 
 @pytest.mark.parametrize("T", [150_000, 64 * 16384 + 5000])
 def test_scoring_of_long_contexts(T):
-    """Ten position blocks (LDS gather, every list narrowed by search) and a context beyond 64 blocks, which takes
-    the global-atomic scatter."""
+    """Ten position blocks (segments from the index's block table) and a context beyond the 64 blocks a table covers
+    (every list walked whole by every block's workgroup and filtered)."""
     rng = np.random.default_rng(T)
     H, k, n_feat, nq = 2, 2, 64, 4
     ids = np.stack([strided_ids(rng, T, k, n_feat) for _ in range(H)])
