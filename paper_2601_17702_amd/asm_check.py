@@ -1,0 +1,95 @@
+"""Build-time scan of the fast encoder's compiled assembly.
+
+The fast encoder spells out its MFMA chains and some LDS reads as inline assembly, which the compiler schedules around
+without knowing what the statements are: it does not insert the wait states an MFMA needs, and it may copy a register
+that an LDS read has not filled yet.  The sources keep the required distances by construction; this scan checks the
+generated code for the three ways the compiler could break them, so that a build that would compute wrong values
+fails instead:
+  1. an instruction other than the chain's next MFMA touches an MFMA's destination within 11 wait states of it
+     (an 8-pass MFMA's result may be read after 11; an `s_nop N` counts N + 1);
+  2. a register that an LDS read is still going to fill is touched before the next wait for the LDS counter;
+  3. a vector instruction writes a source of an MFMA fewer than 2 wait states before it.
+"""
+from __future__ import annotations
+
+import re
+
+
+def _regs(tok: str) -> set:
+    out = set()
+    for m in re.finditer(r"v\[(\d+):(\d+)\]", tok):
+        out |= set(range(int(m.group(1)), int(m.group(2)) + 1))
+    for m in re.finditer(r"(?<![\w\[])v(\d+)\b", tok):
+        out.add(int(m.group(1)))
+    return out
+
+
+_FLOW = ("s_cbranch", "s_branch", "s_swappc", "s_setpc", "s_endpgm", "s_barrier")
+
+
+def scan_kernel(lines: list) -> list:
+    """lines: the instructions of one kernel, in order (labels, comments and directives removed)."""
+    found = []
+    pending = set()
+    for i, l in enumerate(lines):
+        if l.startswith("v_mfma"):
+            dst = _regs(l.split(",")[0])
+            ws, j = 0, i + 1
+            while j < len(lines) and ws < 11:
+                n = lines[j]
+                if n.startswith("s_nop"):
+                    ws += int(n.split()[1]) + 1
+                else:
+                    if n.startswith("v_mfma"):
+                        if _regs(n.split(",")[0]) == dst:
+                            break                      # the chain goes on: the hardware handles this dependency
+                    elif n.startswith(_FLOW):
+                        break
+                    elif _regs(n) & dst:
+                        found.append(f"MFMA result touched after {ws} wait states: `{l}` then `{n}`")
+                        break
+                    ws += 1
+                j += 1
+            src = set()
+            for tok in l.split(",")[1:]:
+                src |= _regs(tok)
+            ws, j = 0, i - 1
+            while j >= 0 and ws < 2:
+                n = lines[j]
+                if n.startswith("s_nop"):
+                    ws += int(n.split()[1]) + 1
+                else:
+                    if (n.startswith("v_") and not n.startswith(("v_mfma", "v_cmp")) and _regs(n.split(",")[0]) & src):
+                        found.append(f"MFMA source written {ws} wait states before it: `{n}` then `{l}`")
+                        break
+                    ws += 1
+                j -= 1
+        if l.startswith("ds_read"):
+            pending |= _regs(l.split(",")[0])
+        elif l.startswith("s_waitcnt") and "lgkmcnt(0)" in l:
+            pending = set()
+        elif l.startswith("s_swappc") and pending:
+            found.append(f"call while LDS reads are in flight: `{l}`")
+        elif pending and not l.startswith(_FLOW) and (_regs(l) & pending):
+            found.append(f"register of an LDS read in flight touched: `{l}`")
+    return found
+
+
+def scan_file(path: str, kernel_filter: str) -> dict:
+    """Scan every kernel of the assembly file whose symbol contains kernel_filter.  Returns {symbol: findings}."""
+    out, name, cur = {}, None, []
+    for raw in open(path):
+        t = raw.strip()
+        m = re.match(r"^(\w+):\s*(;.*)?$", t)
+        if m and not t.startswith(".L") and raw[0] not in " \t":
+            if name is not None:
+                out[name] = scan_kernel(cur)
+            name, cur = (m.group(1) if kernel_filter in m.group(1) else None), []
+            continue
+        if name is None or not t or t.startswith((";", ".", "//")) or t.endswith(":"):
+            continue
+        cur.append(t)
+        if t.startswith("s_endpgm"):
+            out[name] = scan_kernel(cur)
+            name, cur = None, []
+    return out

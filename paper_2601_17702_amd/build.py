@@ -30,9 +30,30 @@ def build(verbose: bool = False, tuning_lib: str | None = None) -> str:
             raise RuntimeError(f"hipcc failed on {s}:\n{err}")
         if verbose and err.strip():
             print(err)
+    check_fast_encoder_asm(extra)
     out = tuning_lib or LIB
     subprocess.check_call(["hipcc", "--offload-arch=gfx950", "-shared", "-fPIC", "-o", out, *objs])
     return out
+
+
+def check_fast_encoder_asm(extra=()) -> None:
+    """Compile the fast encoder to assembly once more and scan it (asm_check): its inline-assembly MFMA chains rely on
+    distances that the compiler does not know about, so a build whose generated code breaks them is rejected."""
+    import tempfile
+    from . import asm_check
+    src = os.path.join(CSRC, "encode_topk_fast.hip")
+    with tempfile.TemporaryDirectory() as tmp:
+        asm = os.path.join(tmp, "encode_topk_fast.s")
+        p = subprocess.run(["hipcc", *FLAGS, *extra, "-S", "--cuda-device-only", src, "-o", asm], stderr=subprocess.PIPE, text=True)
+        if p.returncode != 0:
+            raise RuntimeError(f"hipcc -S failed on {src}:\n{p.stderr}")
+        res = asm_check.scan_file(asm, "sae_encode_topk_")
+    if len(res) < 4:
+        raise RuntimeError(f"asm check: expected the four fast-encoder kernels, found {sorted(res)}")
+    bad = {k: v for k, v in res.items() if v}
+    if bad:
+        lines = [f"{k}: {len(v)} finding(s), first: {v[0]}" for k, v in bad.items()]
+        raise RuntimeError("asm check of the fast encoder failed:\n" + "\n".join(lines))
 
 
 if __name__ == "__main__":

@@ -13,10 +13,12 @@
 //     (c xor (r & 15)), which makes the 16-byte fragment reads of 16 consecutive rows conflict-free;
 //   - b_enc is copied the same way (fp32) and read as the accumulator's initial value (the first
 //     MFMA's C operand), so the bias costs no vector-ALU instruction;
-//   - the epilogue of a stage takes the 16 hit masks (accumulator > tau, one scalar mask each) back
-//     to back, then walks them with scalar branches; an accumulator with a survivor somewhere in the
-//     wavefront runs a short append block under that mask.  Each lane owns a fixed list of CAPL slots,
-//     so "list nearly full" is one compare on the lane's write pointer;
+//   - the epilogue of a stage is lane-parallel and runs between the MFMAs of the next stage: every lane
+//     packs the 16 signs of (tau - accumulator) into a hit mask, picks its first hit with a 16-to-1
+//     select tree and appends it under the mask of lanes that have one (no branch per accumulator; the
+//     MFMA chain is spelled out in assembly so that it keeps this interleaving).  A lane with a second
+//     hit in the same stage takes it in a short loop after the chain (one stage in eight has one).
+//     Each lane owns a fixed list of CAPL slots, so "list full" is one compare on its write pointer;
 //   - threshold refreshes are voted per workgroup at the pair barrier, so that all wavefronts
 //     refresh at the same point instead of stalling each other one after the other; the refresh
 //     loads the lane's candidates into registers once and narrows tau there;
@@ -46,7 +48,7 @@ constexpr int NS = DH / 16;      // MFMA K steps per stage
 constexpr int RB = DH * 2;       // bytes of one W row
 constexpr int kStageB = kFT * RB;
 constexpr int kBiasB = 256;      // the 64 fp32 biases of a pair of stages (one wavefront-wide copy)
-constexpr int kGuard = 4;        // appends possible between two fullness checks
+constexpr int kGuard = 4;        // free slots that a refresh leaves in every list at least
 constexpr float kHintMargin = 0.03f;   // streamed calls start 3 % below the carried bound
 constexpr float kRedoMargin = 0.05f;   // bounds of a head that needed the redo pass are lowered by this much more
 constexpr float kPilotMargin = 0.03f;  // bounds taken from the pilot's single tile are lowered by this much more
@@ -155,23 +157,19 @@ namespace k32 {
 #define S3_CFG_WAVES 8
 #define S3_CFG_CAPL 40
 #define S3_CFG_KMAX 32
-#define S3_CFG_ASYNC_B 1      // second-stage fragment reads stay in flight during the epilogue (registers to spare)
 #include "encode_topk_fast_impl.inc"
 #undef S3_CFG_WAVES
 #undef S3_CFG_CAPL
 #undef S3_CFG_KMAX
-#undef S3_CFG_ASYNC_B
 }  // namespace k32
 namespace k64 {
 #define S3_CFG_WAVES 4
 #define S3_CFG_CAPL 80
 #define S3_CFG_KMAX 64
-#define S3_CFG_ASYNC_B 0      // 80-slot register arrays of the refresh leave no registers that are safe from spills
 #include "encode_topk_fast_impl.inc"
 #undef S3_CFG_WAVES
 #undef S3_CFG_CAPL
 #undef S3_CFG_KMAX
-#undef S3_CFG_ASYNC_B
 }  // namespace k64
 
 }  // namespace
@@ -261,7 +259,7 @@ static int fast_dispatch(EncParams p, hipStream_t st) {
 
 #ifdef S3_TUNING
 // Measurement aid of the tuning build: phase cycle sums of the last S3_ENC_ABLATE=16/17 launch.
-extern "C" int s3_debug_profile(unsigned long long* out32) {
+extern "C" __attribute__((visibility("default"))) int s3_debug_profile(unsigned long long* out32) {
     S3_HIP(hipDeviceSynchronize());
     S3_HIP(hipMemcpyFromSymbol(out32, HIP_SYMBOL(s3_prof), sizeof(unsigned long long) * 32));
     return S3_OK;
