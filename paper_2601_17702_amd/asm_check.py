@@ -7,7 +7,8 @@ generated code for the three ways the compiler could break them, so that a build
 fails instead:
   1. an instruction other than the chain's next MFMA touches an MFMA's destination within 11 wait states of it
      (an 8-pass MFMA's result may be read after 11; an `s_nop N` counts N + 1);
-  2. a register that an LDS read is still going to fill is touched before the next wait for the LDS counter;
+  2. a register that an LDS read is still going to fill is touched before a wait on the LDS counter covers that read
+     (the reads of a wavefront complete in order, so `lgkmcnt(N)` leaves the last N in flight);
   3. a vector instruction writes a source of an MFMA fewer than 2 wait states before it.
 """
 from __future__ import annotations
@@ -30,8 +31,9 @@ _FLOW = ("s_cbranch", "s_branch", "s_swappc", "s_setpc", "s_endpgm", "s_barrier"
 def scan_kernel(lines: list) -> list:
     """lines: the instructions of one kernel, in order (labels, comments and directives removed)."""
     found = []
-    pending = set()
+    inflight = []          # destinations of the LDS / scalar-memory operations not yet waited for, in issue order
     for i, l in enumerate(lines):
+        pending = set().union(*inflight) if inflight else set()
         if l.startswith("v_mfma"):
             dst = _regs(l.split(",")[0])
             ws, j = 0, i + 1
@@ -65,9 +67,12 @@ def scan_kernel(lines: list) -> list:
                     ws += 1
                 j -= 1
         if l.startswith("ds_read"):
-            pending |= _regs(l.split(",")[0])
-        elif l.startswith("s_waitcnt") and "lgkmcnt(0)" in l:
-            pending = set()
+            inflight.append(_regs(l.split(",")[0]))
+        elif l.startswith(("ds_", "s_load", "s_memtime", "s_memrealtime", "s_buffer_load")):
+            inflight.append(set())                     # counts on the same counter, fills no vector register
+        elif l.startswith("s_waitcnt") and "lgkmcnt(" in l:
+            n = int(re.search(r"lgkmcnt\((\d+)\)", l).group(1))       # LDS operations complete in order
+            inflight = inflight[len(inflight) - n:] if n else []
         elif l.startswith("s_swappc") and pending:
             found.append(f"call while LDS reads are in flight: `{l}`")
         elif pending and not l.startswith(_FLOW) and (_regs(l) & pending):

@@ -48,8 +48,8 @@ def check_fast_encoder_asm(extra=()) -> None:
         if p.returncode != 0:
             raise RuntimeError(f"hipcc -S failed on {src}:\n{p.stderr}")
         res = asm_check.scan_file(asm, "sae_encode_topk_")
-    if len(res) < 4:
-        raise RuntimeError(f"asm check: expected the four fast-encoder kernels, found {sorted(res)}")
+    if len(res) < 6:
+        raise RuntimeError(f"asm check: expected the six fast-encoder kernels, found {sorted(res)}")
     bad = {k: v for k, v in res.items() if v}
     if bad:
         lines = [f"{k}: {len(v)} finding(s), first: {v[0]}" for k, v in bad.items()]

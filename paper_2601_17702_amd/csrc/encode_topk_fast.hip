@@ -1,6 +1,7 @@
-// Fast path of the fused SAE encoder + Top-k (Sec. 3.3): bf16, d_head = 128, k <= 64,
-// n_feat a multiple of 128.  The kernel body lives in encode_topk_fast_impl.inc and is built twice: 8 wavefronts
-// with 40 list slots per lane for k <= 32, 4 wavefronts with 80 slots per lane for k <= 64.
+// Fast path of the fused SAE encoder + Top-k (Sec. 3.3; k = 128 is the sparsity of App. B.3): bf16, d_head = 128,
+// k <= 128, n_feat a multiple of 128.  The kernel body lives in encode_topk_fast_impl.inc and is built three times:
+// 8 wavefronts with 40 list slots per lane for k <= 32, 4 wavefronts with 80 slots per lane for k <= 64, 2 wavefronts
+// with 140 slots per lane for k <= 128.
 //
 // Same method as the generic kernel (features on the MFMA M axis, per-token threshold tau,
 // candidate lists in LDS, exact selection), laid out for two wavefronts per SIMD:
@@ -152,7 +153,8 @@ __global__ void enc_stream_post_kernel(const unsigned* hint_out, const float* hi
 }
 
 // One build of the kernel per list geometry: 8 wavefronts x 40 slots per lane for k <= 32, 4 wavefronts x 80 slots
-// per lane for k <= 64 (same LDS footprint).
+// per lane for k <= 64 (same LDS footprint), 2 wavefronts x 140 slots per lane for k <= 128 (a lane must be able to
+// hold all k survivors of its token: they may all fall into its half of the features).
 namespace k32 {
 #define S3_CFG_WAVES 8
 #define S3_CFG_CAPL 40
@@ -171,11 +173,20 @@ namespace k64 {
 #undef S3_CFG_CAPL
 #undef S3_CFG_KMAX
 }  // namespace k64
+namespace k128 {
+#define S3_CFG_WAVES 2
+#define S3_CFG_CAPL 140
+#define S3_CFG_KMAX 128
+#include "encode_topk_fast_impl.inc"
+#undef S3_CFG_WAVES
+#undef S3_CFG_CAPL
+#undef S3_CFG_KMAX
+}  // namespace k128
 
 }  // namespace
 
 bool s3_encode_fast_ok(int dtype, int d_head, int n_feat, int k) {
-    return dtype == S3_BF16 && d_head == DH && k <= k64::kMaxK && n_feat % (4 * kFT) == 0;
+    return dtype == S3_BF16 && d_head == DH && k <= k128::kMaxK && n_feat % (4 * kFT) == 0;
 }
 
 static int fast_dispatch(EncParams p, hipStream_t st);
@@ -232,13 +243,15 @@ int s3_encode_fast_stream(EncParams p, float* hint, void* ws, hipStream_t st) {
 }
 
 static int fast_dispatch(EncParams p, hipStream_t st) {
-    const bool small_k = p.k <= k32::kMaxK;
-    p.soft = small_k ? k32::kSoftDefault : k64::kSoftDefault;      // list length that asks for a voted refresh
+    const bool small_k = p.k <= k32::kMaxK, large_k = p.k > k64::kMaxK;
+    p.soft = small_k ? k32::kSoftDefault : (large_k ? k128::kSoftDefault : k64::kSoftDefault);      // list length that asks for a voted refresh
 #ifdef S3_TUNING
-    const int capl = small_k ? k32::CAPL : k64::CAPL;
+    const int capl = small_k ? k32::CAPL : (large_k ? k128::CAPL : k64::CAPL);
     p.soft = env_int("S3_ENC_SOFT", p.soft);                       // 0 = no voted refreshes
     if (p.soft < 0 || p.soft > capl - kGuard) return s3_fail(S3_EINVAL, "s3_sae_encode_topk: bad S3_ENC_SOFT");
-    if (small_k) {
+    if (large_k) {
+        if (p.ablate) return s3_fail(S3_EINVAL, "s3_sae_encode_topk: S3_ENC_ABLATE %d is not built for k > 64", p.ablate);
+    } else if (small_k) {
         switch (p.ablate) {       // parts of the kernel compiled out (results are then meaningless)
             case 0: break;
             case 1: return k32::launch_fast<kNoHits>(p, st);
@@ -254,6 +267,7 @@ static int fast_dispatch(EncParams p, hipStream_t st) {
         }
     }
 #endif
+    if (large_k) return k128::launch_fast<0>(p, st);
     return small_k ? k32::launch_fast<0>(p, st) : k64::launch_fast<0>(p, st);
 }
 

@@ -23,6 +23,10 @@ def test_flags_register_of_lds_read_in_flight():
     assert any("in flight" in f for f in asm_check.scan_kernel(bad))
     ok = ["ds_read_b128 v[4:7], v200 offset:128", "v_add_u32 v9, v9, v10", "s_waitcnt lgkmcnt(0)", "v_mov_b64_e32 v[198:199], v[4:5]"]
     assert asm_check.scan_kernel(ok) == []
+    # reads complete in order: lgkmcnt(1) covers all but the last one
+    part = ["ds_read_b32 v4, v200", "ds_read_b32 v5, v200 offset:4", "s_waitcnt lgkmcnt(1)", "v_add_u32 v6, v4, v4"]
+    assert asm_check.scan_kernel(part) == []
+    assert any("in flight" in f for f in asm_check.scan_kernel(part + ["v_add_u32 v7, v5, v5"]))
     call = ["ds_read_b128 v[4:7], v200", "s_swappc_b64 s[30:31], s[0:1]"]
     assert any("call" in f for f in asm_check.scan_kernel(call))
 
