@@ -344,6 +344,122 @@ int64_t orc_compact_decode(const int32_t* cstart, const uint16_t* delta, int n_f
     return o;
 }
 
+// ---- SAE training step (Sec. 3.3: encoder, Top-K and decoder equations; App. B.3: Adam, learning rate 1e-3,
+// batches of 4096 tokens, k = 128) ----
+// The paper trains the Top-K SAE by reconstruction and states no other term, so the objective taken is the mean
+// squared reconstruction error over the batch, L = sum_t |xhat_t - x_t|^2 / (B d), with
+//     u_t = x_t - b_dec,  z_t = W_enc u_t + b_enc,  (ids, ReLU(z)) = TopK(z_t, k) as in orc_encode_topk,
+//     xhat_t = sum_i zhat_{t,i} W_dec[id_{t,i}] + b_dec.
+// Gradients are those of L with the selection held fixed (the Top-K passes gradient to the selected entries only,
+// ReLU to the positive ones):
+//     g_t = 2 (xhat_t - x_t) / (B d),  dzhat_{t,i} = g_t . W_dec[id],  dz_{t,i} = dzhat_{t,i} [zhat_{t,i} > 0],
+//     dW_dec[f] = sum zhat g_t,  dW_enc[f] = sum dz u_t,  db_enc[f] = sum dz  (sums over the (t, i) with id = f),
+//     db_dec = sum_t (g_t - sum_i dz_{t,i} W_enc[id_{t,i}]).
+// round_bf16 = 1: the encoder sees its operands in the storage format of the inference path, u = bf16(fl32(x - b_dec))
+// and bf16(W_enc) (round to nearest even), and the backward pass uses those same rounded operands (the rounding
+// itself is treated as the identity); 0: nothing is rounded (the form that finite differences can check).
+// ids_in: null, or a selection [B, k] to use instead of the oracle's own (ids of a row distinct, in [0, n_feat)).
+// Parameters are fp64 arrays: w_enc, w_dec [n_feat, d]; b_enc [n_feat]; b_dec [d].  Gradient outputs have the same
+// shapes; ids_out [B, k] (may be null).  Returns 0, or -1 on invalid arguments.
+static float bf16_rne(float v) {
+    uint32_t u;
+    std::memcpy(&u, &v, 4);
+    u += 0x7FFFu + ((u >> 16) & 1u);      // finite inputs only
+    u &= 0xFFFF0000u;
+    float r;
+    std::memcpy(&r, &u, 4);
+    return r;
+}
+
+float orc_bf16_round(float v) { return bf16_rne(v); }
+
+int orc_sae_loss_grad(const float* x, int B, int d, int n_feat, int k, const double* w_enc, const double* b_enc,
+                      const double* w_dec, const double* b_dec, int round_bf16, const int32_t* ids_in,
+                      int32_t* ids_out, double* loss, double* g_w_enc, double* g_b_enc, double* g_w_dec,
+                      double* g_b_dec) {
+    if (B <= 0 || d <= 0 || n_feat <= 0 || k <= 0 || k > n_feat) return -1;
+    std::vector<double> we((size_t)n_feat * d);
+    for (size_t i = 0; i < we.size(); ++i) we[i] = round_bf16 ? (double)bf16_rne((float)w_enc[i]) : w_enc[i];
+    std::fill(g_w_enc, g_w_enc + (size_t)n_feat * d, 0.0);
+    std::fill(g_w_dec, g_w_dec + (size_t)n_feat * d, 0.0);
+    std::fill(g_b_enc, g_b_enc + n_feat, 0.0);
+    std::fill(g_b_dec, g_b_dec + d, 0.0);
+    double total = 0.0;
+    const double scale = 1.0 / ((double)B * d);
+    std::vector<double> u(d), z(n_feat), xh(d), g(d), du(d);
+    std::vector<int32_t> order(n_feat), sel(k);
+    for (int t = 0; t < B; ++t) {
+        for (int c = 0; c < d; ++c) {
+            if (round_bf16) u[c] = (double)bf16_rne(x[(size_t)t * d + c] - (float)b_dec[c]);
+            else u[c] = (double)x[(size_t)t * d + c] - b_dec[c];
+        }
+        if (ids_in) {
+            for (int i = 0; i < k; ++i) {
+                sel[i] = ids_in[(size_t)t * k + i];
+                if (sel[i] < 0 || sel[i] >= n_feat) return -1;
+            }
+        } else {
+            for (int f = 0; f < n_feat; ++f) {
+                double acc = 0.0;
+                for (int c = 0; c < d; ++c) acc += u[c] * we[(size_t)f * d + c];
+                z[f] = acc + b_enc[f];
+                order[f] = f;
+            }
+            std::sort(order.begin(), order.end(), [&](int32_t a, int32_t c) {
+                if (z[a] != z[c]) return z[a] > z[c];
+                return a < c;
+            });
+            for (int i = 0; i < k; ++i) sel[i] = order[i];
+        }
+        std::vector<double> zh(k);
+        for (int i = 0; i < k; ++i) {
+            const int32_t f = sel[i];
+            double acc = 0.0;
+            for (int c = 0; c < d; ++c) acc += u[c] * we[(size_t)f * d + c];
+            zh[i] = std::max(acc + b_enc[f], 0.0);
+            if (ids_out) ids_out[(size_t)t * k + i] = f;
+        }
+        for (int c = 0; c < d; ++c) xh[c] = b_dec[c];
+        for (int i = 0; i < k; ++i)
+            for (int c = 0; c < d; ++c) xh[c] += zh[i] * w_dec[(size_t)sel[i] * d + c];
+        for (int c = 0; c < d; ++c) {
+            const double r = xh[c] - (double)x[(size_t)t * d + c];
+            total += r * r;
+            g[c] = 2.0 * r * scale;
+            du[c] = 0.0;
+        }
+        for (int i = 0; i < k; ++i) {
+            const int32_t f = sel[i];
+            double dzh = 0.0;
+            for (int c = 0; c < d; ++c) dzh += g[c] * w_dec[(size_t)f * d + c];
+            const double dz = zh[i] > 0.0 ? dzh : 0.0;
+            for (int c = 0; c < d; ++c) {
+                g_w_dec[(size_t)f * d + c] += zh[i] * g[c];
+                g_w_enc[(size_t)f * d + c] += dz * u[c];
+                du[c] += dz * we[(size_t)f * d + c];
+            }
+            g_b_enc[f] += dz;
+        }
+        for (int c = 0; c < d; ++c) g_b_dec[c] += g[c] - du[c];
+    }
+    *loss = total * scale;
+    return 0;
+}
+
+// Adam (App. B.3 names the optimiser and the learning rate; beta1, beta2, eps are the caller's): for step t >= 1
+//     m <- b1 m + (1 - b1) g,  v <- b2 v + (1 - b2) g^2,  p <- p - lr (m / (1 - b1^t)) / (sqrt(v / (1 - b2^t)) + eps).
+int orc_adam(double* p, double* m, double* v, const double* grad, int64_t n, double lr, double b1, double b2,
+             double eps, int step) {
+    if (step < 1) return -1;
+    const double c1 = 1.0 - std::pow(b1, (double)step), c2 = 1.0 - std::pow(b2, (double)step);
+    for (int64_t i = 0; i < n; ++i) {
+        m[i] = b1 * m[i] + (1.0 - b1) * grad[i];
+        v[i] = b2 * v[i] + (1.0 - b2) * grad[i] * grad[i];
+        p[i] -= lr * (m[i] / c1) / (std::sqrt(v[i] / c2) + eps);
+    }
+    return 0;
+}
+
 // Number of host threads orc_encode_topk uses (rows are independent; nothing else is threaded).
 int orc_threads(void) {
 #ifdef _OPENMP

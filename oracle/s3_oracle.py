@@ -61,6 +61,11 @@ def lib():
         L.orc_grow_span.restype = None
         L.orc_fuse.argtypes = [i64, vp, vp, C.c_int, vp, i64, C.c_int, C.c_int, vp, vp]
         L.orc_fuse.restype = i64
+        L.orc_bf16_round.argtypes = [C.c_float]
+        L.orc_bf16_round.restype = C.c_float
+        L.orc_sae_loss_grad.argtypes = [vp, C.c_int, C.c_int, C.c_int, C.c_int, vp, vp, vp, vp, C.c_int, vp, vp, vp,
+                                        vp, vp, vp, vp]
+        L.orc_adam.argtypes = [vp, vp, vp, vp, i64, C.c_double, C.c_double, C.c_double, C.c_double, C.c_int]
         _lib = L
     return _lib
 
@@ -270,3 +275,41 @@ def score_dense(ids, qids, qvals, n_feat, max_freq=0):
         w = act * table[which.reshape(-1)]
         S += w[ids[h]].sum(axis=1)
     return S
+
+
+def bf16_round(a):
+    """float32 array rounded to the nearest bf16 value (ties to even), returned as float32."""
+    a = np.ascontiguousarray(a, dtype=np.float32)
+    f = lib().orc_bf16_round
+    return np.array([f(float(v)) for v in a.ravel()], np.float32).reshape(a.shape)
+
+
+def sae_loss_grad(x, w_enc, b_enc, w_dec, b_dec, k, round_bf16, ids_in=None):
+    """Mean squared reconstruction error of the Top-K SAE on the batch x [B, d] (float32) and its gradients with
+    the selection held fixed.  Parameters are float64 arrays (w_enc, w_dec [n_feat, d]; b_enc [n_feat]; b_dec [d]).
+    Returns dict(loss, ids [B, k], g_w_enc, g_b_enc, g_w_dec, g_b_dec)."""
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    w_enc, b_enc, w_dec, b_dec = (np.ascontiguousarray(a, dtype=np.float64) for a in (w_enc, b_enc, w_dec, b_dec))
+    B, d = x.shape
+    n_feat = w_enc.shape[0]
+    assert w_enc.shape == (n_feat, d) and w_dec.shape == (n_feat, d) and b_enc.shape == (n_feat,) and b_dec.shape == (d,)
+    ids = np.empty((B, k), np.int32)
+    loss = np.zeros(1, np.float64)
+    g = [np.empty_like(w_enc), np.empty_like(b_enc), np.empty_like(w_dec), np.empty_like(b_dec)]
+    if ids_in is not None:
+        ids_in = np.ascontiguousarray(ids_in, dtype=np.int32)
+        assert ids_in.shape == (B, k)
+    rc = lib().orc_sae_loss_grad(_p(x), B, d, n_feat, k, _p(w_enc), _p(b_enc), _p(w_dec), _p(b_dec), int(round_bf16),
+                                 _p(ids_in), _p(ids), _p(loss), _p(g[0]), _p(g[1]), _p(g[2]), _p(g[3]))
+    if rc != 0:
+        raise ValueError("orc_sae_loss_grad: invalid arguments")
+    return {"loss": float(loss[0]), "ids": ids, "g_w_enc": g[0], "g_b_enc": g[1], "g_w_dec": g[2], "g_b_dec": g[3]}
+
+
+def adam(p, m, v, grad, lr, b1, b2, eps, step):
+    """One Adam update in place on float64 arrays of one shape."""
+    for a in (p, m, v, grad):
+        assert a.dtype == np.float64 and a.flags.c_contiguous and a.shape == p.shape
+    rc = lib().orc_adam(_p(p), _p(m), _p(v), _p(grad), p.size, lr, b1, b2, eps, int(step))
+    if rc != 0:
+        raise ValueError("orc_adam: step must be >= 1")
