@@ -272,6 +272,41 @@ int s3_fuse_indices(int64_t n_positions, const int32_t* span_lo, const int32_t* 
                     int lead, int tail, unsigned char* mask, int32_t* idx_out, int32_t* n_out, void* ws,
                     size_t ws_bytes, void* stream);
 
+/* ------------------------------------------------------------------------------------------
+ * One training step of the Top-K SAE (Sec. 3.3: encoder, Top-K and decoder equations; App. B.3:
+ * Adam, learning rate 1e-3, batches of 4096 tokens, expansion 128, k = 128).  The paper trains the
+ * SAE by reconstruction and names no other term; the objective taken is the mean squared error
+ *     L = sum_t |xhat_t - x_t|^2 / (B d),   u_t = x_t - b_dec,  (ids, zhat) = TopK(ReLU(W_enc u_t + b_enc), k),
+ *     xhat_t = sum_i zhat_{t,i} W_dec[ids_{t,i}] + b_dec.
+ * The encoder runs as in the retrieval path: on u and W_enc rounded to bf16 (round to nearest
+ * even), fp32 accumulation, exact Top-K (ties: lower id).  The backward pass holds the selection
+ * fixed, passes gradient only to selected entries with zhat > 0, and treats the rounding as the
+ * identity (gradients use the rounded operands).  With g_t = 2 (xhat_t - x_t) / (B d) and
+ * dz_{t,i} = (g_t . W_dec[id]) [zhat_{t,i} > 0]:
+ *     dW_dec[f] = sum zhat g_t,  dW_enc[f] = sum dz u_t,  db_enc[f] = sum dz   (over the (t, i) with id = f),
+ *     db_dec = sum_t (g_t - sum_i dz_{t,i} W_enc[id_{t,i}]).
+ * Then Adam with bias correction on all parameters, step >= 1 (the caller counts the steps):
+ *     m <- beta1 m + (1 - beta1) grad,  v <- beta2 v + (1 - beta2) grad^2,
+ *     p <- p - lr (m / (1 - beta1^step)) / (sqrt(v / (1 - beta2^step)) + eps).
+ * Every sum is taken in a fixed order (per feature in (token, slot) order through an inverted index
+ * of the batch; no atomics): the step is bit-reproducible.
+ *
+ *   x [B, d_head] fp32, device, read only.
+ *   w_enc, w_dec [n_feat, d_head], b_enc [n_feat], b_dec [d_head]: fp32, device, updated in place.
+ *   adam_m, adam_v [P] fp32, device, P = 2 n_feat d_head + n_feat + d_head, in the order
+ *            W_enc | b_enc | W_dec | b_dec; zero before the first step; updated in place.
+ *   loss_out [1] fp32: L before the update.  ids_out [B, k] int32 or NULL: the selection.
+ *   grads_out [P] fp32 or NULL: the gradients, packed like adam_m.
+ *   ws: s3_sae_train_workspace(B, d_head, n_feat, k) bytes (0 for an unsupported shape), 256-byte
+ *       aligned.
+ * Limits: d_head = 128; n_feat a multiple of 128, <= 65536; 1 <= k <= min(128, n_feat);
+ * B * k <= 2^24; lr >= 0; 0 <= beta1, beta2 < 1; eps > 0.  S3_EINVAL / S3_ECAPACITY as elsewhere. */
+size_t s3_sae_train_workspace(int B, int d_head, int n_feat, int k);
+int s3_sae_train_step(const float* x, int B, int d_head, int n_feat, int k, float* w_enc,
+                      float* b_enc, float* w_dec, float* b_dec, float* adam_m, float* adam_v,
+                      float lr, float beta1, float beta2, float eps, int step, float* loss_out,
+                      int32_t* ids_out, float* grads_out, void* ws, size_t ws_bytes, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

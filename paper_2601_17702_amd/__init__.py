@@ -81,6 +81,11 @@ def lib():
         L.s3_coactivate_score_compact_workspace.restype = sz
         L.s3_coactivate_score_compact.argtypes = [vp, vp, vp, ci, i64, ci, ci, i32, ci, vp, vp, vp, vp, vp, sz, vp]
         L.s3_coactivate_score_compact.restype = ci
+        L.s3_sae_train_workspace.argtypes = [ci, ci, ci, ci]
+        L.s3_sae_train_workspace.restype = sz
+        cf = C.c_float
+        L.s3_sae_train_step.argtypes = [vp, ci, ci, ci, ci, vp, vp, vp, vp, vp, vp, cf, cf, cf, cf, ci, vp, vp, vp, vp, sz, vp]
+        L.s3_sae_train_step.restype = ci
         for name in ("s3_sae_encode_topk", "s3_sae_encode_topk_stream", "s3_index_create", "s3_index_append", "s3_index_finalize",
                      "s3_index_csr", "s3_index_build", "s3_coactivate_score"):
             getattr(L, name).restype = ci
@@ -385,3 +390,39 @@ def fuse_indices(n_positions: int, span_lo, span_hi, n_spans, extra=None, lead: 
                                  0 if extra is None else extra.numel(), lead, tail, _ptr(mask), _ptr(idx), _ptr(n_out),
                                  _ptr(ws), ws.numel(), _stream()))
     return mask, idx, n_out
+
+
+class SaeTrainer:
+    """Parameters, Adam moments and workspace of one Top-K SAE on the GPU; step(x) is one s3_sae_train_step.
+    w_enc, w_dec [n_feat, d] / b_enc [n_feat] / b_dec [d]: float32 GPU tensors, updated in place."""
+
+    def __init__(self, w_enc, b_enc, w_dec, b_dec, k: int, batch: int, lr=1e-3, beta1=0.9, beta2=0.999, eps=1e-8):
+        import torch
+        for t in (w_enc, b_enc, w_dec, b_dec):
+            assert t.is_cuda and t.is_contiguous() and t.dtype == torch.float32
+        self.n_feat, self.d = w_enc.shape
+        assert w_dec.shape == w_enc.shape and b_enc.shape == (self.n_feat,) and b_dec.shape == (self.d,)
+        self.w_enc, self.b_enc, self.w_dec, self.b_dec = w_enc, b_enc, w_dec, b_dec
+        self.k, self.batch, self.hyper, self.steps = k, batch, (lr, beta1, beta2, eps), 0
+        self.P = 2 * self.n_feat * self.d + self.n_feat + self.d
+        self.m = torch.zeros(self.P, dtype=torch.float32, device=w_enc.device)
+        self.v = torch.zeros_like(self.m)
+        need = int(lib().s3_sae_train_workspace(batch, self.d, self.n_feat, k))
+        if need == 0:
+            raise S3Error(1, f"s3_sae_train_workspace: shape not supported (batch {batch}, d {self.d}, n_feat {self.n_feat}, k {k})")
+        self.ws = torch.empty(need, dtype=torch.uint8, device=w_enc.device)
+        self.loss = torch.empty(1, dtype=torch.float32, device=w_enc.device)
+
+    def step(self, x, want_ids=False, want_grads=False):
+        """x [batch, d] float32 on the GPU.  Returns (loss tensor [1], ids or None, grads [P] or None)."""
+        import torch
+        assert x.is_cuda and x.is_contiguous() and x.dtype == torch.float32 and x.shape == (self.batch, self.d)
+        ids = torch.empty((self.batch, self.k), dtype=torch.int32, device=x.device) if want_ids else None
+        grads = torch.empty(self.P, dtype=torch.float32, device=x.device) if want_grads else None
+        self.steps += 1
+        lr, b1, b2, eps = self.hyper
+        _check(lib().s3_sae_train_step(_ptr(x), self.batch, self.d, self.n_feat, self.k, _ptr(self.w_enc), _ptr(self.b_enc),
+                                       _ptr(self.w_dec), _ptr(self.b_dec), _ptr(self.m), _ptr(self.v), lr, b1, b2, eps,
+                                       self.steps, _ptr(self.loss), _ptr(ids), _ptr(grads), _ptr(self.ws), self.ws.numel(),
+                                       _stream()))
+        return self.loss, ids, grads

@@ -82,4 +82,17 @@ def test_host_side_argument_validation():
     assert L.s3_sae_encode_topk_stream(*args, one, C.c_void_p(264), need, None) == -1      # workspace alignment
     assert L.s3_sae_encode_topk_stream(*args, one, one, need - 1, None) == -3              # workspace too small
     assert b"s3_sae_encode_topk_stream" in L.s3_last_error()
+    # training step: shapes, hyper-parameters, pointers and the workspace are checked before anything is launched
+    need = L.s3_sae_train_workspace(256, 128, 1024, 16)
+    assert need > 0 and L.s3_sae_train_workspace(256, 64, 1024, 16) == 0 and L.s3_sae_train_workspace(256, 128, 1000, 16) == 0
+    assert L.s3_sae_train_workspace(1 << 20, 128, 1024, 128) == 0                            # B * k > 2^24
+    hyp = (1e-3, 0.9, 0.999, 1e-8)
+    ptrs = (one,) * 6
+
+    def train(B=256, d=128, nf=1024, k=16, hyp=hyp, step=1, x=one, ws=one, ws_bytes=need):
+        return L.s3_sae_train_step(x, B, d, nf, k, *ptrs, *hyp, step, one, None, None, ws, ws_bytes, None)
+    assert train(d=64) == -1 and train(k=129) == -1 and train(nf=1000) == -1 and train(x=None) == -1
+    assert train(step=0) == -1 and train(hyp=(1e-3, 1.0, 0.999, 1e-8)) == -1 and train(hyp=(1e-3, 0.9, 0.999, 0.0)) == -1
+    assert train(ws=C.c_void_p(264)) == -1 and train(ws_bytes=need - 1) == -3
+    assert b"s3_sae_train_step" in L.s3_last_error()
     assert s3.MAX_K == 128 and s3.MAX_FEAT == 65536
