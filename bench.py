@@ -37,6 +37,36 @@ def measured_traffic(workload: str):
     return None, None
 
 
+def train_leg(torch, s3, steps):
+    """One Adam step of the Top-K SAE at App. B.3's configuration (4096 tokens per batch, expansion 128 -> 16384
+    latents, k = 128, d_head 128) on synthetic activations (a 24-dimensional Gaussian subspace plus noise; unit-norm
+    Gaussian dictionary, decoder initialised next to the encoder): not part of a hot-path step, reported beside it."""
+    Bt, nf, d, k = 4096, 16384, 128, 128
+    g = torch.Generator(device="cuda")
+    g.manual_seed(7)
+    basis = torch.randn(24, d, generator=g, device="cuda") / 24 ** 0.5
+    xs = [torch.randn(Bt, 24, generator=g, device="cuda") @ basis + 0.3 * torch.randn(Bt, d, generator=g, device="cuda")
+          for _ in range(4)]
+    w_enc = torch.randn(nf, d, generator=g, device="cuda")
+    w_enc /= w_enc.norm(dim=1, keepdim=True)
+    w_dec = w_enc + 0.05 * torch.randn(nf, d, generator=g, device="cuda")
+    tr = s3.SaeTrainer(w_enc.contiguous(), torch.zeros(nf, device="cuda"), w_dec.contiguous(), torch.zeros(d, device="cuda"),
+                       k=k, batch=Bt)
+    for i in range(2):
+        tr.step(xs[i])
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    first = float(tr.loss.item())
+    e0.record()
+    for i in range(steps):
+        tr.step(xs[i % 4])
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / steps
+    return {"config": {"batch_tokens": Bt, "n_feat": nf, "k": k, "d_head": d, "optimizer": "adam"}, "steps": steps,
+            "ms_per_step": ms, "tokens_per_s": Bt / (ms * 1e-3),
+            "encoder_gemm_tflops": 2.0 * Bt * nf * d / (ms * 1e-3) / 1e12, "loss_first": first, "loss_last": float(tr.loss.item())}
+
+
 def gen_inputs(w, torch, threads=16):
     """All chunks of all heads, W_enc, b_enc and the queries, generated on the host and moved to HBM."""
     from concurrent.futures import ThreadPoolExecutor
@@ -100,6 +130,9 @@ def main():
     ap.add_argument("--cpu-sample-tokens", type=int, default=0, help="0 = min(L, 32768)")
     ap.add_argument("--cpu-sample-heads", type=int, default=3)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--train-steps", type=int, default=10,
+                    help="SAE training steps timed beside the hot path (App. B.3's configuration; 0 = skip)")
+    ap.add_argument("--train-only", action="store_true", help="time the SAE training steps alone (for profiles)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also launch one plain 256 MiB device copy (a kernel of known traffic, for counter runs)")
     args = ap.parse_args()
@@ -109,6 +142,9 @@ def main():
     import torch
     import paper_2601_17702_amd as s3
     s3.lib()                                   # fail loudly if the HIP library is not built
+    if args.train_only:
+        print(json.dumps({"sae_train_step": train_leg(torch, s3, max(args.train_steps, 1))}))
+        return
     w = synth.WORKLOADS[args.workload]
     H = w.n_heads
     K, W, B, Q = gen_inputs(w, torch)
@@ -245,6 +281,8 @@ def main():
                           "plain_csr_bytes": H * (w.L * w.k + w.n_feat + 1) * 4},
         "spans_found": int(out[2].item()),
     }
+    if args.train_steps > 0:
+        res["sae_train_step"] = train_leg(torch, s3, args.train_steps)
     if not args.no_cpu_baseline:
         res["cpu_baseline"] = cpu_baseline(w, args.cpu_sample_tokens or min(w.L, 32768), args.cpu_sample_heads)
     print(json.dumps(res))
