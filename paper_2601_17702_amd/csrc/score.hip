@@ -175,8 +175,8 @@ __global__ __launch_bounds__(kPrepThreads) void sc_prep_kernel(ScoreArgs a) {
 // vectors are walked one at a time by the whole wavefront, the others G lanes per segment (64 / G segments per load
 // instruction); G is picked on the host from the mean segment length.
 constexpr int kScatterThreads = 1024;
-constexpr int kLong = 4;             // 16-byte loads per lane in flight while a long segment is walked by the whole wavefront
-constexpr int kShortSlots = 4;       // 16-byte loads per lane in flight while short segments are walked by lane groups
+constexpr int kLong = 4;             // vector loads per lane in flight while a long segment is walked by the whole wavefront
+constexpr int kShortSlots = 4;       // vector loads per lane in flight while short segments are walked by lane groups
 constexpr int kNarrowMin = 128;      // sorted lists longer than this are narrowed to the position block by search
 constexpr int kMaxPB = 1 << kS3PosBlockLog2;
 
@@ -204,11 +204,13 @@ __device__ __forceinline__ int lower_bound_pos(const int32_t* pos, int b, int e,
     return b + c;
 }
 
-// element j of a 16-byte vector of postings (int32: 4 per vector; uint16: 8), as an unsigned position value
-template <typename Posting>
+// element j of a vector of four postings (int32: a 16-byte vector; uint16: an 8-byte one), as an unsigned position value
 __device__ __forceinline__ unsigned vec_posting(const uint4& v, int j) {
     const unsigned w[4] = {v.x, v.y, v.z, v.w};
-    if (sizeof(Posting) == 4) return w[j];
+    return w[j];
+}
+__device__ __forceinline__ unsigned vec_posting(const uint2& v, int j) {
+    const unsigned w[2] = {v.x, v.y};
     return (w[j >> 1] >> ((j & 1) * 16)) & 0xFFFFu;
 }
 
@@ -292,11 +294,14 @@ __global__ __launch_bounds__(kScatterThreads) void sc_scatter_lds_kernel(ScoreAr
             // this batch's segments (the part of each list that lies in the block) go to the wavefront's records
             const int n = wf ? max(e - b, 0) : 0;
             recs[lane] = make_int4(b, n, (int)(unsigned)wf, (int)(unsigned)(wf >> 32));
-            // Every load is an aligned 16-byte vector (EPV postings): a segment is read from the 16-byte boundary
-            // at or before its first posting, and the elements in front of it and behind its end are masked out
-            // (they lie in the same 16 bytes as a posting of the array, hence inside the array's allocation).
-            constexpr int EPV = 16 / (int)sizeof(Posting);
-            const int nv = n ? (int)(((((uintptr_t)(pos + b)) & 15) / sizeof(Posting) + n + EPV - 1) / EPV) : 0;
+            // Every load is an aligned vector of four postings (16 bytes of int32, 8 bytes of uint16: as many loads in
+            // flight per posting either way, half the bytes for the compact index): a segment is read from the vector
+            // boundary at or before its first posting, and the elements in front of it and behind its end are masked
+            // out (they lie in the same vector as a posting of the array, hence inside the array's allocation).
+            constexpr int EPV = 4;
+            constexpr int VB = EPV * (int)sizeof(Posting);
+            using Vec = typename std::conditional<sizeof(Posting) == 4, uint4, uint2>::type;
+            const int nv = n ? (int)(((((uintptr_t)(pos + b)) & (VB - 1)) / sizeof(Posting) + n + EPV - 1) / EPV) : 0;
             // long segments (more than 2 G vectors): one at a time, the whole wavefront, kLong vectors in flight per lane
             unsigned long long ml = __ballot(nv > 2 * G);
             while (ml) {
@@ -306,22 +311,22 @@ __global__ __launch_bounds__(kScatterThreads) void sc_scatter_lds_kernel(ScoreAr
                 const unsigned long long w = ((unsigned long long)(unsigned)__builtin_amdgcn_readlane((int)(unsigned)(wf >> 32), src) << 32) |
                                              (unsigned)__builtin_amdgcn_readlane((int)(unsigned)wf, src);
                 const uintptr_t addr = (uintptr_t)(pos + sb);                       // uniform
-                const int shift = (int)((addr & 15) / sizeof(Posting));
-                const uint4* vp = (const uint4*)(addr & ~(uintptr_t)15);
+                const int shift = (int)((addr & (VB - 1)) / sizeof(Posting));
+                const Vec* vp = (const Vec*)(addr & ~(uintptr_t)(VB - 1));
                 const int total = shift + sn, nvec = (total + EPV - 1) / EPV;
                 for (int v0 = 0; v0 < nvec; v0 += 64 * kLong) {
-                    uint4 raw[kLong];
+                    Vec raw[kLong];
 #pragma unroll
                     for (int u = 0; u < kLong; ++u) {
                         const int vi = v0 + u * 64 + lane;
-                        raw[u] = vi < nvec ? vp[vi] : make_uint4(0, 0, 0, 0);
+                        raw[u] = vi < nvec ? vp[vi] : Vec{};
                     }
 #pragma unroll
                     for (int u = 0; u < kLong; ++u) {
                         const int el0 = (v0 + u * 64 + lane) * EPV;
 #pragma unroll
                         for (int j = 0; j < EPV; ++j) {
-                            const unsigned rr = vec_posting<Posting>(raw[u], j) - pbase;
+                            const unsigned rr = vec_posting(raw[u], j) - pbase;
                             if (el0 + j >= shift && el0 + j < total && rr < span) atomicAdd(&sblk[rr], w);
                         }
                     }
@@ -346,29 +351,29 @@ __global__ __launch_bounds__(kScatterThreads) void sc_scatter_lds_kernel(ScoreAr
                     }
                     rc[u] = idx >= 0 ? recs[idx] : make_int4(0, 0, 0, 0);
                 }
-                const uint4* vp[kShortSlots];
+                const Vec* vp[kShortSlots];
                 int shift[kShortSlots], total[kShortSlots];
 #pragma unroll
                 for (int u = 0; u < kShortSlots; ++u) {
                     const uintptr_t addr = (uintptr_t)(pos + rc[u].x);
-                    shift[u] = (int)((addr & 15) / sizeof(Posting));
-                    vp[u] = (const uint4*)(addr & ~(uintptr_t)15);
+                    shift[u] = (int)((addr & (VB - 1)) / sizeof(Posting));
+                    vp[u] = (const Vec*)(addr & ~(uintptr_t)(VB - 1));
                     total[u] = rc[u].y ? shift[u] + rc[u].y : 0;
                     two = two || total[u] > G * EPV;
                 }
                 const int chunks = __any(two) ? 2 : 1;
                 for (int c = 0; c < chunks; ++c) {
-                    uint4 raw[kShortSlots];
+                    Vec raw[kShortSlots];
 #pragma unroll
                     for (int u = 0; u < kShortSlots; ++u)
-                        raw[u] = (c * G + sub) * EPV < total[u] ? vp[u][c * G + sub] : make_uint4(0, 0, 0, 0);
+                        raw[u] = (c * G + sub) * EPV < total[u] ? vp[u][c * G + sub] : Vec{};
 #pragma unroll
                     for (int u = 0; u < kShortSlots; ++u) {
                         const unsigned long long w = ((unsigned long long)(unsigned)rc[u].w << 32) | (unsigned)rc[u].z;
                         const int el0 = (c * G + sub) * EPV;
 #pragma unroll
                         for (int j = 0; j < EPV; ++j) {
-                            const unsigned rr = vec_posting<Posting>(raw[u], j) - pbase;
+                            const unsigned rr = vec_posting(raw[u], j) - pbase;
                             if (el0 + j >= shift[u] && el0 + j < total[u] && rr < span) atomicAdd(&sblk[rr], w);
                         }
                     }
@@ -699,7 +704,7 @@ static int score_run(const char* who, const ScoreSource& v, const int32_t* qids,
     // lanes per short segment: from the mean length of a list's part in one position block
     const double mean_seg = (double)v.tokens * a.k / ((double)a.n_feat * l.npb);
     const bool narrow = mean_seg <= 20.0, cmp = v.delta != nullptr;
-    auto scatter = cmp ? (narrow ? sc_scatter_lds_kernel<4, true> : sc_scatter_lds_kernel<8, true>)
+    auto scatter = cmp ? (narrow ? sc_scatter_lds_kernel<8, true> : sc_scatter_lds_kernel<16, true>)
                        : (narrow ? sc_scatter_lds_kernel<8, false> : sc_scatter_lds_kernel<16, false>);
     if (int rc = s3_allow_lds(once_scatter[2 * cmp + narrow], (const void*)scatter, kMaxPB * 8)) return rc;
     // at most five launches: query weights, gather, sum of the head groups, pooling + tile maxima, Top-B
