@@ -3,13 +3,15 @@
 The fast encoder spells out its MFMA chains and some LDS reads as inline assembly, which the compiler schedules around
 without knowing what the statements are: it does not insert the wait states an MFMA needs, and it may copy a register
 that an LDS read has not filled yet.  The sources keep the required distances by construction; this scan checks the
-generated code for the three ways the compiler could break them, so that a build that would compute wrong values
+generated code for the four ways the compiler could break them, so that a build that would compute wrong values
 fails instead:
   1. an instruction other than the chain's next MFMA touches an MFMA's destination within 11 wait states of it
      (an 8-pass MFMA's result may be read after 11; an `s_nop N` counts N + 1);
   2. a register that an LDS read is still going to fill is touched before a wait on the LDS counter covers that read
      (the reads of a wavefront complete in order, so `lgkmcnt(N)` leaves the last N in flight);
-  3. a vector instruction writes a source of an MFMA fewer than 2 wait states before it.
+  3. a vector instruction writes a source of an MFMA fewer than 2 wait states before it;
+  4. a partial wait (`lgkmcnt(N)`, N > 0) is relied on for an LDS read while a scalar-memory load is in flight
+     (those count on the same counter and return out of order, which makes the count meaningless).
 """
 from __future__ import annotations
 
@@ -32,6 +34,7 @@ def scan_kernel(lines: list) -> list:
     """lines: the instructions of one kernel, in order (labels, comments and directives removed)."""
     found = []
     inflight = []          # destinations of the LDS / scalar-memory operations not yet waited for, in issue order
+    smem = False           # a scalar-memory operation is among them
     for i, l in enumerate(lines):
         pending = set().union(*inflight) if inflight else set()
         if l.startswith("v_mfma"):
@@ -70,9 +73,13 @@ def scan_kernel(lines: list) -> list:
             inflight.append(_regs(l.split(",")[0]))
         elif l.startswith(("ds_", "s_load", "s_memtime", "s_memrealtime", "s_buffer_load")):
             inflight.append(set())                     # counts on the same counter, fills no vector register
+            smem = smem or l.startswith("s_")
         elif l.startswith("s_waitcnt") and "lgkmcnt(" in l:
             n = int(re.search(r"lgkmcnt\((\d+)\)", l).group(1))       # LDS operations complete in order
+            if n and smem and pending:
+                found.append(f"partial wait with a scalar-memory load in flight: `{l}`")
             inflight = inflight[len(inflight) - n:] if n else []
+            smem = smem and n > 0
         elif l.startswith("s_swappc") and pending:
             found.append(f"call while LDS reads are in flight: `{l}`")
         elif pending and not l.startswith(_FLOW) and (_regs(l) & pending):
