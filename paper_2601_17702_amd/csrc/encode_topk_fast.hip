@@ -50,7 +50,7 @@ constexpr int RB = DH * 2;       // bytes of one W row
 constexpr int kStageB = kFT * RB;
 constexpr int kBiasB = 256;      // the 64 fp32 biases of a pair of stages (one wavefront-wide copy)
 constexpr int kGuard = 4;        // free slots that a refresh leaves in every list at least
-constexpr float kHintMargin = 0.03f;   // streamed calls start 3 % below the carried bound
+constexpr float kHintMargin = 0.04f;   // streamed calls start 4 % below the carried bound
 constexpr float kRedoMargin = 0.05f;   // bounds of a head that needed the redo pass are lowered by this much more
 constexpr float kPilotMargin = 0.03f;  // bounds taken from the pilot's single tile are lowered by this much more
 constexpr int kOffBias = kRing * kStageB;
@@ -65,6 +65,7 @@ typedef __attribute__((address_space(1))) const void glb_cvoid;
 // compile-time ablation masks: the product library instantiates the kernels with 0 only; builds with -DS3_TUNING
 // (measurement tooling, never shipped) also instantiate kernels without appends and with per-phase cycle counters
 constexpr int kNoHits = 1, kProfile = 16;
+constexpr int kFillWGs = 256;      // workgroups that give every compute unit one
 
 #ifdef S3_TUNING
 // kProfile build: cycles per phase, summed over the steps of wavefronts 0 and 4 of workgroup 0
@@ -182,6 +183,15 @@ namespace k128 {
 #undef S3_CFG_CAPL
 #undef S3_CFG_KMAX
 }  // namespace k128
+namespace k128n {      // the same lists in workgroups of one wavefront: twice the workgroups when a call has few tokens
+#define S3_CFG_WAVES 1
+#define S3_CFG_CAPL 140
+#define S3_CFG_KMAX 128
+#include "encode_topk_fast_impl.inc"
+#undef S3_CFG_WAVES
+#undef S3_CFG_CAPL
+#undef S3_CFG_KMAX
+}  // namespace k128n
 
 }  // namespace
 
@@ -267,7 +277,12 @@ static int fast_dispatch(EncParams p, hipStream_t st) {
         }
     }
 #endif
-    if (large_k) return k128::launch_fast<0>(p, st);
+    if (large_k) {
+        // A call whose token tiles would leave most compute units without a workgroup (an SAE training batch: one
+        // head, a few thousand tokens) runs in one-wavefront workgroups instead.
+        const long long tiles = (long long)p.n_heads * ((p.T + k128::kTokWG - 1) / k128::kTokWG);
+        return tiles < kFillWGs ? k128n::launch_fast<0>(p, st) : k128::launch_fast<0>(p, st);
+    }
     return small_k ? k32::launch_fast<0>(p, st) : k64::launch_fast<0>(p, st);
 }
 

@@ -1,5 +1,5 @@
 """The build-time scan of the fast encoder's assembly (paper_2601_17702_amd/asm_check.py) on hand-written snippets:
-it has to flag each of the three patterns it exists for, and to accept the shapes the kernel really has."""
+it has to flag each of the four patterns it exists for, and to accept the shapes the kernel really has."""
 from paper_2601_17702_amd import asm_check
 
 MFMA = "v_mfma_f32_32x32x16_bf16 v[16:31], v[40:43], v[44:47], v[16:31]"
@@ -35,6 +35,20 @@ def test_flags_vector_write_right_before_mfma_source():
     bad = ["v_accvgpr_read_b32 v40, a3", MFMA]
     assert any("source written" in f for f in asm_check.scan_kernel(bad))
     assert asm_check.scan_kernel(["v_accvgpr_read_b32 v40, a3", "s_nop 1", MFMA]) == []
+
+
+def test_flags_partial_wait_with_scalar_load_in_flight():
+    # the chain's own shape: reads issued in a block, each MFMA behind the partial wait that covers its fragment
+    chain = ["s_waitcnt lgkmcnt(0)", "ds_read_b128 v[40:43], v200", "ds_read_b128 v[48:51], v201",
+             "s_waitcnt lgkmcnt(1)", MFMA, "s_waitcnt lgkmcnt(0)",
+             "v_mfma_f32_32x32x16_bf16 v[16:31], v[48:51], v[44:47], v[16:31]"]
+    assert asm_check.scan_kernel(chain) == []
+    # scalar loads count on the same counter and return out of order: a partial wait then proves nothing
+    bad = ["s_load_dwordx2 s[4:5], s[0:1], 0x0"] + chain[1:]
+    assert any("scalar-memory" in f for f in asm_check.scan_kernel(bad))
+    # a fragment consumed before its wait
+    early = chain[:3] + [MFMA]
+    assert any("in flight" in f for f in asm_check.scan_kernel(early))
 
 
 def test_scan_file_splits_kernels(tmp_path):
