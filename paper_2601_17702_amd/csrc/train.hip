@@ -66,20 +66,46 @@ struct TokArgs {
     float scale;          // 2 / (B d)
 };
 
-// Step 3: one wavefront per token; lane l holds columns 2 l and 2 l + 1.
+// Step 3: one wavefront per token; lane l holds columns 2 l and 2 l + 1.  The token's ids and values are read once
+// (entry i in lane i % 64, register i / 64; k <= 128) and handed out by readlane, and the decoder rows are fetched
+// four at a time, so that no load waits for the previous row's arithmetic; the sums keep the order of the entries.
 __global__ __launch_bounds__(kTokThreads) void tr_token_kernel(TokArgs a) {
     const int lane = threadIdx.x & 63;
     const int t = blockIdx.x * (kTokThreads / 64) + (threadIdx.x >> 6);
     if (t >= a.B) return;
-    const int32_t* ids = a.ids + (size_t)t * a.k;
-    const float* vals = a.vals + (size_t)t * a.k;
+    const int32_t* __restrict__ ids = a.ids + (size_t)t * a.k;
+    const float* __restrict__ vals = a.vals + (size_t)t * a.k;
+    const float* __restrict__ w_dec = a.w_dec;
+    const uint16_t* __restrict__ w_bf = a.w_bf;
+    int my_id[2];
+    float my_v[2];
+#pragma unroll
+    for (int r = 0; r < 2; ++r) {
+        const int i = lane + 64 * r;
+        my_id[r] = i < a.k ? ids[i] : 0;
+        my_v[r] = i < a.k ? vals[i] : 0.f;
+    }
     const float2 xv = *(const float2*)(a.x + (size_t)t * DH + 2 * lane);
     float2 acc = *(const float2*)(a.b_dec + 2 * lane);
-    for (int i = 0; i < a.k; ++i) {
-        const float v = vals[i];
-        const float2 row = *(const float2*)(a.w_dec + (size_t)ids[i] * DH + 2 * lane);
-        acc.x += v * row.x;
-        acc.y += v * row.y;
+#pragma unroll
+    for (int r = 0; r < 2; ++r) {
+        const int kk = min(a.k - 64 * r, 64);
+        for (int i0 = 0; i0 < kk; i0 += 4) {
+            float2 row[4];
+            float v[4];
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {        // entries past the end repeat the group's first one with value 0
+                const int i = i0 + q < kk ? i0 + q : i0;
+                const int f = __builtin_amdgcn_readlane(my_id[r], i);
+                v[q] = i0 + q < kk ? __int_as_float(__builtin_amdgcn_readlane(__float_as_int(my_v[r]), i)) : 0.f;
+                row[q] = *(const float2*)(w_dec + (size_t)f * DH + 2 * lane);
+            }
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                acc.x += v[q] * row[q].x;
+                acc.y += v[q] * row[q].y;
+            }
+        }
     }
     const float rx = acc.x - xv.x, ry = acc.y - xv.y;
     const float part = wave_sum(rx * rx + ry * ry);
@@ -87,15 +113,34 @@ __global__ __launch_bounds__(kTokThreads) void tr_token_kernel(TokArgs a) {
     const float gx = rx * a.scale, gy = ry * a.scale;
     *(float2*)(a.g + (size_t)t * DH + 2 * lane) = make_float2(gx, gy);
     float dux = 0.f, duy = 0.f;
-    for (int i = 0; i < a.k; ++i) {
-        const int32_t f = ids[i];
-        const float2 row = *(const float2*)(a.w_dec + (size_t)f * DH + 2 * lane);
-        const float dot = wave_sum(gx * row.x + gy * row.y);
-        const float dz = vals[i] > 0.f ? dot : 0.f;
-        if (lane == 0) a.dz[(size_t)t * a.k + i] = dz;
-        const uint32_t we = *(const uint32_t*)(a.w_bf + (size_t)f * DH + 2 * lane);
-        dux += dz * __uint_as_float(we << 16);
-        duy += dz * __uint_as_float(we & 0xFFFF0000u);
+    float* __restrict__ dz_out = a.dz + (size_t)t * a.k;
+#pragma unroll
+    for (int r = 0; r < 2; ++r) {
+        const int kk = min(a.k - 64 * r, 64);
+        for (int i0 = 0; i0 < kk; i0 += 4) {
+            float2 row[4];
+            uint32_t we[4];
+            float v[4], dz[4];
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int i = i0 + q < kk ? i0 + q : i0;
+                const int f = __builtin_amdgcn_readlane(my_id[r], i);
+                v[q] = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(my_v[r]), i));
+                row[q] = *(const float2*)(w_dec + (size_t)f * DH + 2 * lane);
+                we[q] = *(const uint32_t*)(w_bf + (size_t)f * DH + 2 * lane);
+            }
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {        // four independent reductions: their lane shifts interleave
+                const float dot = wave_sum(gx * row[q].x + gy * row[q].y);
+                dz[q] = (i0 + q < kk && v[q] > 0.f) ? dot : 0.f;
+            }
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                if (lane == 0 && i0 + q < kk) dz_out[64 * r + i0 + q] = dz[q];
+                dux += dz[q] * __uint_as_float(we[q] << 16);
+                duy += dz[q] * __uint_as_float(we[q] & 0xFFFF0000u);
+            }
+        }
     }
     *(float2*)(a.du + (size_t)t * DH + 2 * lane) = make_float2(dux, duy);
 }
@@ -132,17 +177,27 @@ __global__ __launch_bounds__(kTokThreads) void tr_feature_kernel(FeatArgs a) {
             my_v = a.vals[s];
             my_dz = a.dz[s];
         }
-        for (int q = 0; q < n; ++q) {
-            const int t = __builtin_amdgcn_readlane(my_t, q);
-            const float v = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(my_v), q));
-            const float dz = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(my_dz), q));
-            const float2 gv = *(const float2*)(a.g + (size_t)t * DH + 2 * lane);
-            const uint32_t uu = *(const uint32_t*)(a.u_bf + (size_t)t * DH + 2 * lane);
-            dx += v * gv.x;
-            dy += v * gv.y;
-            ex += dz * __uint_as_float(uu << 16);
-            ey += dz * __uint_as_float(uu & 0xFFFF0000u);
-            sb += dz;
+        for (int q0 = 0; q0 < n; q0 += 4) {      // four postings' rows in flight; the sums keep the posting order
+            float2 gv[4];
+            uint32_t uu[4];
+            float v[4], dz[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {        // postings past the end repeat the last one with weights 0
+                const int q = min(q0 + j, n - 1);
+                const int t = __builtin_amdgcn_readlane(my_t, q);
+                v[j] = q0 + j < n ? __int_as_float(__builtin_amdgcn_readlane(__float_as_int(my_v), q)) : 0.f;
+                dz[j] = q0 + j < n ? __int_as_float(__builtin_amdgcn_readlane(__float_as_int(my_dz), q)) : 0.f;
+                gv[j] = *(const float2*)(a.g + (size_t)t * DH + 2 * lane);
+                uu[j] = *(const uint32_t*)(a.u_bf + (size_t)t * DH + 2 * lane);
+            }
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                dx += v[j] * gv[j].x;
+                dy += v[j] * gv[j].y;
+                ex += dz[j] * __uint_as_float(uu[j] << 16);
+                ey += dz[j] * __uint_as_float(uu[j] & 0xFFFF0000u);
+                sb += dz[j];
+            }
         }
     }
     *(float2*)(a.g_w_enc + (size_t)f * DH + 2 * lane) = make_float2(ex, ey);
@@ -163,16 +218,29 @@ __global__ __launch_bounds__(DH) void tr_colpart_kernel(const float* g, const fl
         losspart[blockIdx.x] = l;
     }
 }
-// second half: the chunks in order
-__global__ __launch_bounds__(DH) void tr_colfin_kernel(const float* colpart, const double* losspart, int nchunk,
-                                                       double inv_n, float* g_b_dec, float* loss_out) {
+// second half: the chunks in order (eight loads in flight; the loss parts are summed by a wavefront of their own)
+__global__ __launch_bounds__(2 * DH) void tr_colfin_kernel(const float* __restrict__ colpart, const double* __restrict__ losspart,
+                                                           int nchunk, double inv_n, float* g_b_dec, float* loss_out) {
     const int c = threadIdx.x;
-    float s = 0.f;
-    for (int q = 0; q < nchunk; ++q) s += colpart[(size_t)q * DH + c];
-    g_b_dec[c] = s;
-    if (c == 0) {
+    if (c < DH) {
+        float s = 0.f;
+        for (int q0 = 0; q0 < nchunk; q0 += 8) {
+            float v[8];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) v[j] = q0 + j < nchunk ? colpart[(size_t)(q0 + j) * DH + c] : 0.f;
+#pragma unroll
+            for (int j = 0; j < 8; ++j) s += v[j];
+        }
+        g_b_dec[c] = s;
+    } else if (c == DH) {
         double l = 0.0;
-        for (int q = 0; q < nchunk; ++q) l += losspart[q];
+        for (int q0 = 0; q0 < nchunk; q0 += 8) {
+            double v[8];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) v[j] = q0 + j < nchunk ? losspart[q0 + j] : 0.0;
+#pragma unroll
+            for (int j = 0; j < 8; ++j) l += v[j];
+        }
         loss_out[0] = (float)(l * inv_n);
     }
 }
@@ -293,7 +361,7 @@ int s3_sae_train_step(const float* x, int B, int d_head, int n_feat, int k, floa
     const int nchunk = (B + kChunk - 1) / kChunk;
     hipLaunchKernelGGL(tr_colpart_kernel, dim3((unsigned)nchunk), dim3(DH), 0, st, (const float*)g, (const float*)du,
                        (const double*)lossp, B, colpart, losspart);
-    hipLaunchKernelGGL(tr_colfin_kernel, dim3(1), dim3(DH), 0, st, (const float*)colpart, (const double*)losspart, nchunk,
+    hipLaunchKernelGGL(tr_colfin_kernel, dim3(1), dim3(2 * DH), 0, st, (const float*)colpart, (const double*)losspart, nchunk,
                        1.0 / ((double)B * DH), g_b_dec, loss_out);
     AdamArgs aa;
     aa.p[0] = w_enc; aa.p[1] = b_enc; aa.p[2] = w_dec; aa.p[3] = b_dec;
