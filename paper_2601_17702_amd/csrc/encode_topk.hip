@@ -397,6 +397,7 @@ static int encode_impl(const char* who, const void* x, int dtype, int T, int d_h
     p.x = (const char*)x; p.w = (const char*)w_enc; p.b = b_enc; p.ids = ids; p.vals = vals;
     p.T = T; p.n_feat = n_feat; p.k = k; p.n_heads = n_heads;
     p.ablate = 0;
+    p.fsplit = 1;
     bool fast = s3_encode_fast_ok(dtype, d_head, n_feat, k);
 #ifdef S3_TUNING
     p.ablate = env_int("S3_ENC_ABLATE", 0);

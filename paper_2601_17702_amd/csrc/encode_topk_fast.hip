@@ -207,6 +207,69 @@ int s3_encode_fast_launch(EncParams p, hipStream_t st) {
     return fast_dispatch(p, st);
 }
 
+// Merge of the two halves' Top-k of one token (each sorted by pre-activation descending, feature id ascending; no key
+// occurs twice): an entry's place is its place in its own list plus the number of entries of the other list in front
+// of it, found by bisection.  One wavefront per (head, token), two entries of each list per lane (k <= 128).
+__global__ __launch_bounds__(256) void enc_merge2_kernel(const int32_t* __restrict__ part_ids, const float* __restrict__ part_vals,
+                                                         int n_heads, int T, int k, int32_t* __restrict__ ids,
+                                                         float* __restrict__ vals) {
+    __shared__ unsigned skey[4][2][128];
+    __shared__ int sid[4][2][128];
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    const long long row = (long long)blockIdx.x * 4 + w;           // head * T + token
+    const bool live = row < (long long)n_heads * T;
+    const int head = live ? (int)(row / T) : 0, tok = live ? (int)(row % T) : 0;
+    for (int l = 0; l < 2; ++l) {
+        const size_t src = (((size_t)(2 * head + l)) * T + tok) * k;
+        for (int e = lane; e < k; e += 64) {
+            skey[w][l][e] = live ? ordered_key(part_vals[src + e]) : 0u;
+            sid[w][l][e] = live ? part_ids[src + e] : 0;
+        }
+    }
+    __syncthreads();
+    if (!live) return;
+    const size_t dst = (size_t)row * k;
+    for (int l = 0; l < 2; ++l) {
+        const unsigned* okey = skey[w][l ^ 1];
+        const int* oid = sid[w][l ^ 1];
+        for (int e = lane; e < k; e += 64) {
+            const unsigned kv = skey[w][l][e];
+            const int id = sid[w][l][e];
+            int lo = 0, hi = k;                                    // entries of the other list in front of this one
+            while (lo < hi) {
+                const int mid = (lo + hi) >> 1;
+                const bool before = okey[mid] > kv || (okey[mid] == kv && oid[mid] < id);
+                if (before) lo = mid + 1; else hi = mid;
+            }
+            const int rank = e + lo;
+            if (rank < k) {
+                ids[dst + rank] = id;
+                vals[dst + rank] = fmaxf(key_value(kv), 0.f);
+            }
+        }
+    }
+}
+
+bool s3_encode_fast_split_pays(int n_heads, int T, int n_feat, int k) {
+    if (k <= k64::kMaxK || k > k128::kMaxK || n_feat % 256 != 0 || n_feat / 2 < k) return false;   // built for the k <= 128 lists only
+    const long long tiles = (long long)n_heads * ((T + k128n::kTokWG - 1) / k128n::kTokWG);
+    return 2 * tiles <= kFillWGs;
+}
+
+int s3_encode_fast_split(EncParams p, int32_t* part_ids, float* part_vals, hipStream_t st) {
+    int32_t* ids = p.ids;
+    float* vals = p.vals;
+    const int n_heads = p.n_heads;
+    p.ids = part_ids; p.vals = part_vals;
+    p.n_heads = 2 * n_heads; p.n_feat /= 2; p.fsplit = 2;
+    if (int rc = s3_encode_fast_launch(p, st)) return rc;
+    const long long rows = (long long)n_heads * p.T;
+    hipLaunchKernelGGL(enc_merge2_kernel, dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, st, (const int32_t*)part_ids,
+                       (const float*)part_vals, n_heads, p.T, p.k, ids, vals);
+    S3_HIP(hipGetLastError());
+    return S3_OK;
+}
+
 size_t s3_encode_fast_stream_workspace(int n_heads, int T) {
     return s3_align((size_t)n_heads * 4) + 2 * s3_align((size_t)n_heads * 8) + s3_align((size_t)n_heads * 12) +
            s3_align((size_t)n_heads * T * 4);

@@ -115,6 +115,8 @@ struct EncParams {
     int headroom;  // generic kernel: free list slots per token required before a run of appends (32, or 16 for k > 64)
     int ablate;    // tuning builds (-DS3_TUNING) only: parts of the kernel compiled out; always 0 in the product
     int soft;      // fast path: list length per lane that asks for a workgroup-wide refresh (0: off)
+    int fsplit;    // fast path, plain calls: 1, or F > 1 = the call's heads are F feature ranges of each real head (head h reads
+                   // the tokens of head h / F, its feature ids start at (h % F) * n_feat, values leave without the ReLU)
     // streamed calls (threshold carried from the previous chunk), fast path only
     float margin;              // relative margin below the carried bound
     int mode;                  // 0 plain, 1 start from the carried bound, 2 redo the tokens listed in redo_list,
@@ -132,6 +134,10 @@ int env_int(const char* name, int dflt);      // tuning knobs are read from the 
 #endif
 bool s3_encode_fast_ok(int dtype, int d_head, int n_feat, int k);   // shapes the fast kernel is built for
 int s3_encode_fast_launch(EncParams p, hipStream_t st);
+// The same result by two launches' worth of workgroups: every head's features in two halves, each half's Top-k into
+// part_ids / part_vals ([2 n_heads][T][k] each), then merged.  For calls with too few token tiles to fill the chip.
+bool s3_encode_fast_split_pays(int n_heads, int T, int n_feat, int k);
+int s3_encode_fast_split(EncParams p, int32_t* part_ids, float* part_vals, hipStream_t st);
 size_t s3_encode_fast_stream_workspace(int n_heads, int T);
 int s3_encode_fast_stream(EncParams p, float* hint, void* ws, hipStream_t st);   // hint [n_heads][2] device, in/out
 

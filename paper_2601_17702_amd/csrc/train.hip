@@ -268,7 +268,7 @@ __global__ void tr_adam_kernel(AdamArgs a) {
 }
 
 struct Layout {
-    size_t u_bf, w_bf, ids, vals, g, dz, du, lossp, offsets, slots, grads, colpart, losspart, iws, total, iws_bytes;
+    size_t u_bf, w_bf, ids, vals, part_ids, part_vals, g, dz, du, lossp, offsets, slots, grads, colpart, losspart, iws, total, iws_bytes;
 };
 
 Layout layout(int B, int n_feat, int k) {
@@ -281,6 +281,9 @@ Layout layout(int B, int n_feat, int k) {
     L.w_bf = take((size_t)n_feat * DH * 2);
     L.ids = take((size_t)B * k * 4);
     L.vals = take((size_t)B * k * 4);
+    const bool split = s3_encode_fast_split_pays(1, B, n_feat, k);     // the encoder then runs on two halves of the features
+    L.part_ids = take(split ? (size_t)2 * B * k * 4 : 0);
+    L.part_vals = take(split ? (size_t)2 * B * k * 4 : 0);
     L.g = take((size_t)B * DH * 4);
     L.dz = take((size_t)B * k * 4);
     L.du = take((size_t)B * DH * 4);
@@ -345,7 +348,16 @@ int s3_sae_train_step(const float* x, int B, int d_head, int n_feat, int k, floa
 
     hipLaunchKernelGGL(tr_prep_kernel, dim3((unsigned)((n_max + 255) / 256)), dim3(256), 0, st, x, (const float*)b_dec,
                        (const float*)w_enc, u_bf, w_bf, n_x, n_w);
-    int rc = s3_sae_encode_topk(u_bf, S3_BF16, B, DH, w_bf, b_enc, n_feat, k, 1, ids, vals, stream);
+    int rc;
+    if (s3_encode_fast_split_pays(1, B, n_feat, k)) {
+        // one head and a few thousand tokens are too few token tiles for the chip: the features go in two halves
+        EncParams p;
+        p.x = (const char*)u_bf; p.w = (const char*)w_bf; p.b = b_enc; p.ids = ids; p.vals = vals;
+        p.T = B; p.n_feat = n_feat; p.k = k; p.n_heads = 1; p.ablate = 0; p.fsplit = 1;
+        rc = s3_encode_fast_split(p, (int32_t*)(base + L.part_ids), (float*)(base + L.part_vals), st);
+    } else {
+        rc = s3_sae_encode_topk(u_bf, S3_BF16, B, DH, w_bf, b_enc, n_feat, k, 1, ids, vals, stream);
+    }
     if (rc) return rc;
     TokArgs ta{x, w_dec, b_dec, w_bf, ids, vals, g, dz, du, lossp, B, k, 2.0f / ((float)B * (float)DH)};
     hipLaunchKernelGGL(tr_token_kernel, dim3((unsigned)((B + 3) / 4)), dim3(kTokThreads), 0, st, ta);
