@@ -3,7 +3,7 @@
 The fast encoder spells out its MFMA chains and some LDS reads as inline assembly, which the compiler schedules around
 without knowing what the statements are: it does not insert the wait states an MFMA needs, and it may copy a register
 that an LDS read has not filled yet.  The sources keep the required distances by construction; this scan checks the
-generated code for the four ways the compiler could break them, so that a build that would compute wrong values
+generated code for the five ways the compiler could break them, so that a build that would compute wrong values
 fails instead:
   1. an instruction other than the chain's next MFMA touches an MFMA's destination within 11 wait states of it
      (an 8-pass MFMA's result may be read after 11; an `s_nop N` counts N + 1);
@@ -11,7 +11,10 @@ fails instead:
      (the reads of a wavefront complete in order, so `lgkmcnt(N)` leaves the last N in flight);
   3. a vector instruction writes a source of an MFMA fewer than 2 wait states before it;
   4. a partial wait (`lgkmcnt(N)`, N > 0) is relied on for an LDS read while a scalar-memory load is in flight
-     (those count on the same counter and return out of order, which makes the count meaningless).
+     (those count on the same counter and return out of order, which makes the count meaningless);
+  5. compiler-generated code reads SCC (`s_cselect`, `s_cbranch_scc*`, add/subtract with carry) when the last
+     instruction that wrote it lies inside an inline-assembly statement: the statement changes SCC without saying so
+     in its clobber list, and the compiler kept a condition in it across the statement.
 """
 from __future__ import annotations
 
@@ -28,11 +31,36 @@ def _regs(tok: str) -> set:
 
 
 _FLOW = ("s_cbranch", "s_branch", "s_swappc", "s_setpc", "s_endpgm", "s_barrier")
+_ASM_BEGIN, _ASM_END = "#asm_begin", "#asm_end"      # markers of inline-assembly statements (kept by scan_file)
+_SCC_WRITERS = ("s_cmp", "s_and", "s_or", "s_xor", "s_nand", "s_nor", "s_xnor", "s_add", "s_sub", "s_lshl", "s_lshr",
+                "s_ashr", "s_bfe", "s_abs", "s_min", "s_max", "s_not", "s_wqm", "s_bcnt", "s_bitcmp", "s_quadmask")
+_SCC_READERS = ("s_cselect", "s_cbranch_scc", "s_addc", "s_subb", "s_cmov")
+
+
+def _scan_scc(lines: list) -> list:
+    found, in_asm, written_in_asm = [], False, False
+    for l in lines:
+        if l == _ASM_BEGIN:
+            in_asm = True
+        elif l == _ASM_END:
+            in_asm = False
+        elif l.startswith(_SCC_READERS):
+            if written_in_asm and not in_asm:
+                found.append(f"SCC read after an inline-assembly statement wrote it: `{l}`")
+                written_in_asm = False
+            if l.startswith(("s_addc", "s_subb")):          # these write it as well
+                written_in_asm = in_asm
+        elif l.startswith(_SCC_WRITERS):
+            written_in_asm = in_asm
+        elif l.startswith(("s_swappc", "s_setpc")):
+            written_in_asm = False                           # SCC does not survive a call
+    return found
 
 
 def scan_kernel(lines: list) -> list:
     """lines: the instructions of one kernel, in order (labels, comments and directives removed)."""
-    found = []
+    found = _scan_scc(lines)
+    lines = [l for l in lines if l not in (_ASM_BEGIN, _ASM_END)]
     inflight = []          # destinations of the LDS / scalar-memory operations not yet waited for, in issue order
     smem = False           # a scalar-memory operation is among them
     for i, l in enumerate(lines):
@@ -98,6 +126,10 @@ def scan_file(path: str, kernel_filter: str) -> dict:
                 out[name] = scan_kernel(cur)
             name, cur = (m.group(1) if kernel_filter in m.group(1) else None), []
             continue
+        if name is not None and t.startswith(";;#ASMSTART"):
+            cur.append(_ASM_BEGIN)
+        elif name is not None and t.startswith(";;#ASMEND"):
+            cur.append(_ASM_END)
         if name is None or not t or t.startswith((";", ".", "//")) or t.endswith(":"):
             continue
         cur.append(t)

@@ -1,5 +1,5 @@
 """The build-time scan of the fast encoder's assembly (paper_2601_17702_amd/asm_check.py) on hand-written snippets:
-it has to flag each of the four patterns it exists for, and to accept the shapes the kernel really has."""
+it has to flag each of the five patterns it exists for, and to accept the shapes the kernel really has."""
 from paper_2601_17702_amd import asm_check
 
 MFMA = "v_mfma_f32_32x32x16_bf16 v[16:31], v[40:43], v[44:47], v[16:31]"
@@ -49,6 +49,17 @@ def test_flags_partial_wait_with_scalar_load_in_flight():
     # a fragment consumed before its wait
     early = chain[:3] + [MFMA]
     assert any("in flight" in f for f in asm_check.scan_kernel(early))
+
+
+def test_flags_scc_kept_across_an_asm_statement_that_writes_it():
+    blk = ["#asm_begin", "v_cmp_eq_u32 vcc, v1, v2", "s_or_b64 s[0:1], s[0:1], vcc", "#asm_end"]
+    bad = ["s_cmp_eq_u32 s4, 0"] + blk + ["s_cselect_b64 vcc, -1, 0"]
+    assert any("SCC" in f for f in asm_check.scan_kernel(bad))
+    # the compiler compares again behind the statement: fine
+    assert asm_check.scan_kernel(["s_cmp_eq_u32 s4, 0"] + blk + ["s_cmp_eq_u32 s4, 0", "s_cselect_b64 vcc, -1, 0"]) == []
+    # a statement that leaves SCC alone
+    ok = ["s_cmp_eq_u32 s4, 0", "#asm_begin", "v_add_u32 v1, v1, v2", "#asm_end", "s_cbranch_scc1 .LBB0_2"]
+    assert asm_check.scan_kernel(ok) == []
 
 
 def test_scan_file_splits_kernels(tmp_path):
