@@ -124,8 +124,8 @@ def cpu_baseline(w, sample_tokens, sample_heads):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=3)
-    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="c2_llama8b", choices=sorted(synth.WORKLOADS))
     ap.add_argument("--cpu-sample-tokens", type=int, default=0, help="0 = min(L, 32768)")
     ap.add_argument("--cpu-sample-heads", type=int, default=3)
